@@ -1,0 +1,153 @@
+/*
+ * shflbw - Shfl-BW (shuffled block-wise) sparse weight x dense activation
+ * product for AMD MI355X (gfx950), C ABI.
+ *
+ * Problem statement (Algorithm 1 of the paper: data A.row_indices,
+ * A.metadata, A.values, B[K][N]; result C[M][N]; Section 4.3: both dense
+ * matrices are row-major with the batch/token dimension innermost):
+ *
+ *     Y[M][N] = (W .* mask)[M][K] * X[K][N]
+ *
+ * where the mask is a Shfl-BW pattern (Section 3.1): after the row
+ * permutation `perm`, every group of V consecutive stored rows keeps the
+ * same set of columns.  `perm[i]` is the ORIGINAL row of stored row i: stored
+ * row i holds W[perm[i]] and its result is written to Y[perm[i]]
+ * (reordered write-back, Section 4.2).
+ *
+ * General rules
+ *  - Every function returns an int status: SHFLBW_OK (0) or a negative
+ *    shflbw_status.  Nothing aborts or throws across this boundary.  A short
+ *    text for the last failure on the calling thread is kept in
+ *    shflbw_last_error().
+ *  - "host" pointers are ordinary process memory; "device" pointers are HIP
+ *    device memory of the current device.  The library never allocates device
+ *    memory: the packed matrix lives in a caller-owned device buffer that
+ *    must outlive every call using it.
+ *  - shflbw_spmm / shflbw_conv2d only enqueue work on the given HIP stream
+ *    (a hipStream_t passed as void*; NULL = the default stream) and return
+ *    without synchronising.  Launch errors are returned; execution errors
+ *    surface at the caller's next synchronisation.
+ *  - Y / out are fully overwritten (no accumulate-into).
+ *  - Activations and weights are IEEE binary16; products are accumulated in
+ *    binary32 on the matrix cores; the result is rounded once to the
+ *    requested output type.
+ */
+#ifndef SHFLBW_H
+#define SHFLBW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct shflbw_matrix shflbw_matrix; /* opaque; owns host copies of the packed arrays */
+
+typedef enum {
+    SHFLBW_F16 = 0, /* IEEE binary16 */
+    SHFLBW_F32 = 2  /* IEEE binary32 (output only) */
+} shflbw_dtype;
+
+typedef enum {
+    SHFLBW_NCHW = 0, /* x innermost */
+    SHFLBW_CHWN = 1  /* batch innermost: the layout the paper assumes (Section 4.3) */
+} shflbw_layout;
+
+typedef enum {
+    SHFLBW_OK = 0,
+    SHFLBW_ERR_NULL_ARG = -1,      /* a required pointer is NULL */
+    SHFLBW_ERR_BAD_SHAPE = -2,     /* M % V != 0, unsupported V, non-positive size, leading dimension too small, ... */
+    SHFLBW_ERR_BAD_PERM = -3,      /* perm is not a permutation of 0..M-1 */
+    SHFLBW_ERR_BAD_PATTERN = -4,   /* mask differs inside a permuted row group; detail in shflbw_last_error() */
+    SHFLBW_ERR_BAD_DTYPE = -5,     /* dtype enum not supported for this argument */
+    SHFLBW_ERR_NOT_ON_DEVICE = -6, /* spmm/conv2d before shflbw_bind_device */
+    SHFLBW_ERR_HIP = -7,           /* a HIP runtime call failed; text in shflbw_last_error() */
+    SHFLBW_ERR_NO_MEMORY = -8,     /* host allocation failed */
+    SHFLBW_ERR_BAD_OPTION = -9     /* unknown tuning value */
+} shflbw_status;
+
+/*
+ * Offline step (a) of Section 4.1-4.3 (host only, no GPU needed): check the
+ * pattern, reorder the rows into vector-wise form, keep the original row
+ * indices, and store the kept V x 1 vectors stitched into V x T_K tiles in
+ * the order the matrix cores consume them.
+ *
+ *  W     host, M x K binary16, row-major, leading dimension ldw >= K (elements).
+ *  mask  host, M x K bytes, row-major, leading dimension K; non-zero = kept.
+ *        NULL: a V x 1 vector is kept iff any of its V weights is non-zero.
+ *        Kept weights whose value is zero are stored like any other.
+ *  perm  host, M int32; NULL = identity.
+ *  V     rows per group: 16, 32, 64 or 128.  M must be a multiple of V.
+ *  out   receives a new handle; release it with shflbw_destroy.
+ * Groups may keep different numbers of columns, including none.
+ */
+int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* perm,
+                    int M, int K, int V, shflbw_dtype wdtype, shflbw_matrix** out);
+
+void shflbw_destroy(shflbw_matrix* A);
+
+/* Shape and sparsity of a packed matrix.  Any out pointer may be NULL.
+ * nnz counts kept weights (V per kept vector, no padding);
+ * sparsity = 1 - nnz / (M*K). */
+int shflbw_info(const shflbw_matrix* A, int* M, int* K, int* V, int* groups,
+                int64_t* nnz, double* sparsity);
+
+/* Test hooks that expose the logical vector-wise form (host only).
+ * shflbw_row_indices: copies the M original-row indices (Section 4.2).
+ * shflbw_group_columns: writes the ascending kept columns of group g into
+ *   cols[0..cap) and returns their count (>= 0), or a negative status; with
+ *   cols == NULL it only returns the count.
+ * shflbw_decompress: writes (W .* mask) as M x K binary16 with leading
+ *   dimension ldw, original row order; bitwise equal to the masked input. */
+int shflbw_row_indices(const shflbw_matrix* A, int32_t* rows_out);
+int shflbw_group_columns(const shflbw_matrix* A, int g, int32_t* cols, int cap);
+int shflbw_decompress(const shflbw_matrix* A, void* W_out, int ldw);
+
+/* Bytes of device memory the packed matrix needs (multiple of 256). */
+size_t shflbw_device_bytes(const shflbw_matrix* A);
+
+/* Copy the packed arrays into dev_buf (device, caller-owned, at least
+ * shflbw_device_bytes(A) bytes, 256-byte aligned) on `stream` and remember
+ * the address.  The copy is complete when the call returns. */
+int shflbw_bind_device(shflbw_matrix* A, void* dev_buf, void* stream);
+
+/* Kernel selection, for measurement.  kernel: 0 = automatic, 1 = per-wave
+ * gather kernel.  tile_n: 0 = automatic, else the number of output columns
+ * one wavefront owns (64 or 128). */
+int shflbw_set_tuning(shflbw_matrix* A, int kernel, int tile_n);
+
+/*
+ * Linear layer (Algorithm 1: BulkLoadMeta / StitchTile / WarpMMA loop, then
+ * ReorderedWriteBack):  Y = (W .* mask) X.
+ *  X  device, K x N binary16, row-major, leading dimension ldx >= N.
+ *  Y  device, M x N of ydtype (SHFLBW_F16 or SHFLBW_F32), leading dimension
+ *     ldy >= N.  Must not overlap X.
+ * N == 0 is a no-op.  Groups without kept columns produce zero rows.
+ * Fast path: N, ldx, ldy multiples of 8 and 16-byte aligned bases; other
+ * shapes take a slower element-wise path with the same result.
+ */
+int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int64_t ldy,
+                int64_t N, shflbw_dtype ydtype, void* stream);
+
+/*
+ * 2-D convolution as implicit GEMM (Section 4.1): the unfolded feature map
+ * exists only in on-chip buffers.  A has M = C_out rows and K = C_in*R*S
+ * columns flattened as k = (c*R + r)*S + s.  Cross-correlation (no kernel
+ * flip), zero padding, dilation 1, groups 1.
+ *  in   device, binary16: [batch][C_in][H][W] (NCHW) or [C_in][H][W][batch] (CHWN).
+ *  out  device, ydtype:   [batch][C_out][H_out][W_out] or [C_out][H_out][W_out][batch],
+ *       H_out = (H + 2*pad_h - R)/stride_h + 1, W_out likewise.
+ */
+int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out,
+                  int batch, int C_in, int H, int W, int R, int S,
+                  int stride_h, int stride_w, int pad_h, int pad_w,
+                  shflbw_layout layout, shflbw_dtype ydtype, void* stream);
+
+const char* shflbw_status_string(int status);
+const char* shflbw_last_error(void); /* thread-local, never NULL */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHFLBW_H */

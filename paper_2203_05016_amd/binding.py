@@ -1,0 +1,221 @@
+"""Thin ctypes binding of the shflbw C ABI (see ``include/shflbw.h``).
+
+Argument marshalling only: every step of the hot path runs inside the
+library's kernels.  torch tensors are used for device memory and for the
+stream handle; numpy arrays for host-side inputs of the compressor.
+
+The library is required: if ``libshflbw.so`` has not been built this module
+raises at first use.  There is no CPU fallback.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+F16, F32 = 0, 2
+NCHW, CHWN = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libshflbw.so")
+_lib = None
+
+EXPORTS = [
+    "shflbw_compress", "shflbw_destroy", "shflbw_info", "shflbw_row_indices",
+    "shflbw_group_columns", "shflbw_decompress", "shflbw_device_bytes", "shflbw_bind_device",
+    "shflbw_set_tuning", "shflbw_spmm", "shflbw_conv2d", "shflbw_status_string",
+    "shflbw_last_error",
+]
+
+
+class ShflbwError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("shflbw status %d (%s): %s" % (status, status_string(status), text))
+        self.status = status
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("%s is missing: build it with `python -m paper_2203_05016_amd.build`"
+                               % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        L.shflbw_compress.restype = i32
+        L.shflbw_compress.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, ctypes.POINTER(vp)]
+        L.shflbw_destroy.restype = None
+        L.shflbw_destroy.argtypes = [vp]
+        L.shflbw_info.restype = i32
+        L.shflbw_info.argtypes = [vp] + [ctypes.POINTER(i32)] * 4 + \
+            [ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
+        L.shflbw_row_indices.restype = i32
+        L.shflbw_row_indices.argtypes = [vp, vp]
+        L.shflbw_group_columns.restype = i32
+        L.shflbw_group_columns.argtypes = [vp, i32, vp, i32]
+        L.shflbw_decompress.restype = i32
+        L.shflbw_decompress.argtypes = [vp, vp, i32]
+        L.shflbw_device_bytes.restype = ctypes.c_size_t
+        L.shflbw_device_bytes.argtypes = [vp]
+        L.shflbw_bind_device.restype = i32
+        L.shflbw_bind_device.argtypes = [vp, vp, vp]
+        L.shflbw_set_tuning.restype = i32
+        L.shflbw_set_tuning.argtypes = [vp, i32, i32]
+        L.shflbw_spmm.restype = i32
+        L.shflbw_spmm.argtypes = [vp, vp, i64, vp, i64, i64, i32, vp]
+        L.shflbw_conv2d.restype = i32
+        L.shflbw_conv2d.argtypes = [vp, vp, vp] + [i32] * 10 + [i32, i32, vp]
+        L.shflbw_status_string.restype = ctypes.c_char_p
+        L.shflbw_status_string.argtypes = [i32]
+        L.shflbw_last_error.restype = ctypes.c_char_p
+        L.shflbw_last_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().shflbw_status_string(int(status)).decode()
+
+
+def last_error():
+    return lib().shflbw_last_error().decode()
+
+
+def _check(rc):
+    if rc < 0:
+        raise ShflbwError(rc, last_error())
+    return rc
+
+
+def _host_ptr(a):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ydtype(t):
+    import torch
+    if t.dtype == torch.float16:
+        return F16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError("output tensor must be float16 or float32")
+
+
+class Matrix:
+    """Owner of one ``shflbw_matrix`` handle and, once bound, of the device
+    buffer (a torch uint8 tensor) that holds its packed arrays."""
+
+    def __init__(self, handle):
+        self._h = handle
+        self._dev = None
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and _lib is not None:
+            _lib.shflbw_destroy(h)
+
+    # -- host side
+    def info(self):
+        M, K, V, G = (ctypes.c_int() for _ in range(4))
+        nnz, sp = ctypes.c_int64(), ctypes.c_double()
+        _check(lib().shflbw_info(self._h, M, K, V, G, nnz, sp))
+        return dict(M=M.value, K=K.value, V=V.value, groups=G.value, nnz=nnz.value,
+                    sparsity=sp.value)
+
+    def row_indices(self):
+        out = np.empty(self.info()["M"], dtype=np.int32)
+        _check(lib().shflbw_row_indices(self._h, _host_ptr(out)))
+        return out
+
+    def group_columns(self, g):
+        n = _check(lib().shflbw_group_columns(self._h, g, None, 0))
+        out = np.empty(n, dtype=np.int32)
+        if n:
+            _check(lib().shflbw_group_columns(self._h, g, _host_ptr(out), n))
+        return out
+
+    def decompress(self, ldw=None):
+        i = self.info()
+        ldw = i["K"] if ldw is None else ldw
+        out = np.zeros((i["M"], ldw), dtype=np.float16)
+        _check(lib().shflbw_decompress(self._h, _host_ptr(out), ldw))
+        return out
+
+    def device_bytes(self):
+        return int(lib().shflbw_device_bytes(self._h))
+
+    def set_tuning(self, kernel=0, tile_n=0):
+        _check(lib().shflbw_set_tuning(self._h, kernel, tile_n))
+
+    # -- device side
+    def bind_device(self, device="cuda:0", stream=None):
+        import torch
+        buf = torch.empty(self.device_bytes(), dtype=torch.uint8, device=device)
+        _check(lib().shflbw_bind_device(self._h, ctypes.c_void_p(buf.data_ptr()),
+                                        _stream_ptr(stream)))
+        self._dev = buf
+        return self
+
+    def spmm(self, X, Y=None, out_dtype=None, stream=None):
+        """Y = (W . mask) X for a device tensor X of shape (K, N), float16."""
+        import torch
+        if X.dtype != torch.float16 or X.dim() != 2 or X.stride(1) != 1 and X.shape[1] > 1:
+            raise TypeError("X must be a 2-D float16 tensor with unit column stride")
+        N = X.shape[1]
+        if Y is None:
+            Y = torch.empty((self.info()["M"], N), dtype=out_dtype or torch.float16,
+                            device=X.device)
+        ldx = X.stride(0) if X.shape[0] > 1 else max(N, 1)
+        ldy = Y.stride(0) if Y.shape[0] > 1 else max(N, 1)
+        _check(lib().shflbw_spmm(self._h, ctypes.c_void_p(X.data_ptr()), ldx,
+                                 ctypes.c_void_p(Y.data_ptr()), ldy, N, _ydtype(Y),
+                                 _stream_ptr(stream)))
+        return Y
+
+    def conv2d(self, inp, R, S, stride=(1, 1), pad=(0, 0), layout="NCHW", out=None,
+               out_dtype=None, stream=None):
+        """Masked conv2d of a contiguous float16 device tensor."""
+        import torch
+        if inp.dtype != torch.float16 or not inp.is_contiguous():
+            raise TypeError("input must be a contiguous float16 tensor")
+        if layout == "NCHW":
+            B, C, H, W = inp.shape
+        else:
+            C, H, W, B = inp.shape
+        Ho = (H + 2 * pad[0] - R) // stride[0] + 1
+        Wo = (W + 2 * pad[1] - S) // stride[1] + 1
+        Cout = self.info()["M"]
+        shape = (B, Cout, Ho, Wo) if layout == "NCHW" else (Cout, Ho, Wo, B)
+        if out is None:
+            out = torch.empty(shape, dtype=out_dtype or torch.float16, device=inp.device)
+        _check(lib().shflbw_conv2d(self._h, ctypes.c_void_p(inp.data_ptr()),
+                                   ctypes.c_void_p(out.data_ptr()), B, C, H, W, R, S,
+                                   stride[0], stride[1], pad[0], pad[1],
+                                   NCHW if layout == "NCHW" else CHWN, _ydtype(out),
+                                   _stream_ptr(stream)))
+        return out
+
+
+def compress(W, mask, perm, V, K=None):
+    """shflbw_compress on numpy arrays: W (M, ldw) float16 of which the first K
+    columns are the matrix (default: all), mask (M, K) uint8 or None, perm
+    (M,) int32 or None."""
+    if W.dtype != np.float16 or W.ndim != 2:
+        raise TypeError("W must be a 2-D float16 array")
+    W = np.ascontiguousarray(W)
+    M, ldw = W.shape
+    K = ldw if K is None else K
+    m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
+    p = None if perm is None else np.ascontiguousarray(perm, dtype=np.int32)
+    if m is not None and m.shape != (M, K):
+        raise ValueError("mask shape")
+    if p is not None and p.shape != (M,):
+        raise ValueError("perm shape")
+    h = ctypes.c_void_p()
+    _check(lib().shflbw_compress(_host_ptr(W), ldw, _host_ptr(m), _host_ptr(p), M, K, V, F16,
+                                 ctypes.byref(h)))
+    return Matrix(h)

@@ -1,0 +1,180 @@
+// Device-facing entry points of the C ABI: binding the packed matrix to a
+// caller-owned device buffer, and the launchers of the SpMM / conv2d kernels.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <string>
+
+#include "gather_kernel.hip"
+#include "shflbw_internal.h"
+
+namespace shflbw {
+namespace {
+
+int hip_fail(hipError_t e, const char* what)
+{
+    return fail(SHFLBW_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+PackedView view_of(const shflbw_matrix* A)
+{
+    const char* b = static_cast<const char*>(A->dev_base);
+    PackedView v;
+    v.row_indices = reinterpret_cast<const int32_t*>(b + A->off_rows);
+    v.step_ptr = reinterpret_cast<const int32_t*>(b + A->off_steps);
+    v.col_idx = reinterpret_cast<const int32_t*>(b + A->off_cols);
+    v.values = reinterpret_cast<const half8*>(b + A->off_vals);
+    v.G = A->G;
+    return v;
+}
+
+template <int V, int WN, typename OutT, class Geom>
+int launch_gather(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t stream)
+{
+    constexpr int WAVES = 4, PD = 2;
+    const long n_tiles = (N + WN - 1) / WN;
+    const long gx = (n_tiles + WAVES - 1) / WAVES;
+    if (gx > 0x7fffffffL || A->G > 65535) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
+    dim3 grid((unsigned)gx, (unsigned)A->G, 1), block(64 * WAVES, 1, 1);
+    hipLaunchKernelGGL((shflbw_gather_kernel<V, WN, WAVES, PD, OutT, Geom>), grid, block, 0, stream,
+                       view_of(A), geom, (int)n_tiles);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return SHFLBW_OK;
+}
+
+template <int V, typename OutT, class Geom>
+int dispatch_wn(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t stream)
+{
+    int wn = A->tune_tile_n;
+    if (wn == 0) wn = (V >= 128) ? 64 : 128;
+    if (V >= 128 && wn == 128) wn = 64;  // 4 row blocks x 4 tiles of accumulators do not fit
+    if (wn == 64) return launch_gather<V, 64, OutT, Geom>(A, geom, N, stream);
+    return launch_gather<(V >= 128 ? 64 : V), 128, OutT, Geom>(A, geom, N, stream);
+}
+
+template <typename OutT, class Geom>
+int dispatch_v(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t stream)
+{
+    switch (A->V) {
+        case 16: return dispatch_wn<16, OutT, Geom>(A, geom, N, stream);
+        case 32: return dispatch_wn<32, OutT, Geom>(A, geom, N, stream);
+        case 64: return dispatch_wn<64, OutT, Geom>(A, geom, N, stream);
+        case 128: return dispatch_wn<128, OutT, Geom>(A, geom, N, stream);
+    }
+    return fail(SHFLBW_ERR_BAD_SHAPE, "unsupported V");
+}
+
+template <class Geom>
+int dispatch_out(const shflbw_matrix* A, const Geom& geom, long N, shflbw_dtype ydtype,
+                 hipStream_t stream)
+{
+    if (ydtype == SHFLBW_F16) return dispatch_v<_Float16, Geom>(A, geom, N, stream);
+    return dispatch_v<float, Geom>(A, geom, N, stream);
+}
+
+int check_bound(const shflbw_matrix* A)
+{
+    if (!A->dev_base) return fail(SHFLBW_ERR_NOT_ON_DEVICE, "call shflbw_bind_device first");
+    return SHFLBW_OK;
+}
+
+}  // namespace
+}  // namespace shflbw
+
+extern "C" {
+
+int shflbw_bind_device(shflbw_matrix* A, void* dev_buf, void* stream)
+{
+    using namespace shflbw;
+    if (!A || !dev_buf) return fail(SHFLBW_ERR_NULL_ARG, "NULL argument");
+    if (reinterpret_cast<uintptr_t>(dev_buf) % 256)
+        return fail(SHFLBW_ERR_BAD_SHAPE, "dev_buf must be 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* b = static_cast<char*>(dev_buf);
+    struct Part { size_t off; const void* src; size_t bytes; };
+    const Part parts[] = {
+        {A->off_rows, A->row_indices.data(), A->row_indices.size() * sizeof(int32_t)},
+        {A->off_steps, A->step_ptr.data(), A->step_ptr.size() * sizeof(int32_t)},
+        {A->off_cols, A->col_idx.data(), A->col_idx.size() * sizeof(int32_t)},
+        {A->off_vals, A->values.data(), A->values.size() * sizeof(uint16_t)},
+    };
+    for (const Part& p : parts) {
+        if (!p.bytes) continue;
+        hipError_t e = hipMemcpyAsync(b + p.off, p.src, p.bytes, hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync");
+    }
+    hipError_t e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    A->dev_base = dev_buf;
+    return SHFLBW_OK;
+}
+
+int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int64_t ldy,
+                int64_t N, shflbw_dtype ydtype, void* stream)
+{
+    using namespace shflbw;
+    if (!A) return fail(SHFLBW_ERR_NULL_ARG, "A is NULL");
+    if (ydtype != SHFLBW_F16 && ydtype != SHFLBW_F32)
+        return fail(SHFLBW_ERR_BAD_DTYPE, "ydtype must be SHFLBW_F16 or SHFLBW_F32");
+    if (N < 0) return fail(SHFLBW_ERR_BAD_SHAPE, "N < 0");
+    if (N == 0) return SHFLBW_OK;
+    if (!X || !Y) return fail(SHFLBW_ERR_NULL_ARG, "X and Y must not be NULL");
+    if (ldx < N || ldy < N) return fail(SHFLBW_ERR_BAD_SHAPE, "leading dimension smaller than N");
+    if (N > (int64_t)1 << 40) return fail(SHFLBW_ERR_BAD_SHAPE, "N too large");
+    int rc = check_bound(A);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool aligned = (N % 8 == 0) && (ldx % 8 == 0) && (ldy % 8 == 0) &&
+                         (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
+    if (aligned) {
+        GeomLinear<true> g{static_cast<const _Float16*>(X), Y, (long)ldx, (long)ldy, (long)N};
+        return dispatch_out(A, g, (long)N, ydtype, st);
+    }
+    GeomLinear<false> g{static_cast<const _Float16*>(X), Y, (long)ldx, (long)ldy, (long)N};
+    return dispatch_out(A, g, (long)N, ydtype, st);
+}
+
+int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, int C_in, int H,
+                  int W, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
+                  shflbw_layout layout, shflbw_dtype ydtype, void* stream)
+{
+    using namespace shflbw;
+    if (!A) return fail(SHFLBW_ERR_NULL_ARG, "A is NULL");
+    if (ydtype != SHFLBW_F16 && ydtype != SHFLBW_F32)
+        return fail(SHFLBW_ERR_BAD_DTYPE, "ydtype must be SHFLBW_F16 or SHFLBW_F32");
+    if (layout != SHFLBW_NCHW && layout != SHFLBW_CHWN)
+        return fail(SHFLBW_ERR_BAD_SHAPE, "unknown layout");
+    if (batch < 0 || C_in <= 0 || H <= 0 || W <= 0 || R <= 0 || S <= 0 || stride_h <= 0 ||
+        stride_w <= 0 || pad_h < 0 || pad_w < 0)
+        return fail(SHFLBW_ERR_BAD_SHAPE, "non-positive convolution dimension");
+    if ((int64_t)C_in * R * S != A->K)
+        return fail(SHFLBW_ERR_BAD_SHAPE, "C_in*R*S does not match the packed matrix's K");
+    if (H + 2 * pad_h < R || W + 2 * pad_w < S)
+        return fail(SHFLBW_ERR_BAD_SHAPE, "kernel larger than the padded input");
+    if (H + 2 * pad_h > 32767 || W + 2 * pad_w > 32767)
+        return fail(SHFLBW_ERR_BAD_SHAPE, "padded image side above 32767");
+    const int Ho = (H + 2 * pad_h - R) / stride_h + 1;
+    const int Wo = (W + 2 * pad_w - S) / stride_w + 1;
+    const int64_t N = (int64_t)batch * Ho * Wo;
+    if (N == 0) return SHFLBW_OK;
+    if (!in || !out) return fail(SHFLBW_ERR_NULL_ARG, "in and out must not be NULL");
+    const int64_t lim = (int64_t)1 << 31;
+    // 32-bit element offsets inside the kernel, including the padded halo
+    if ((int64_t)batch * C_in * (H + 2 * pad_h) * (W + 2 * pad_w) >= lim ||
+        (int64_t)A->M * N >= lim)
+        return fail(SHFLBW_ERR_BAD_SHAPE, "tensor above 2^31 elements");
+    int rc = check_bound(A);
+    if (rc) return rc;
+    GeomConv g;
+    g.in = static_cast<const _Float16*>(in);
+    g.out = out;
+    g.B = batch; g.Cin = C_in; g.H = H; g.W = W; g.Cout = A->M; g.R = R; g.S = S;
+    g.sh = stride_h; g.sw = stride_w; g.ph = pad_h; g.pw = pad_w; g.Ho = Ho; g.Wo = Wo;
+    g.chwn = (layout == SHFLBW_CHWN);
+    g.N = N;
+    return dispatch_out(A, g, (long)N, ydtype, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,401 @@
+// Per-wavefront gather kernel for the Shfl-BW product on gfx950 (CDNA4).
+//
+// One wavefront owns one row group (V stored rows) x WN output columns and
+// runs Algorithm 1's loop on its own, with no workgroup barrier:
+//   BulkLoadMeta  - the column indices of a k-step are fetched 2*PD steps
+//                   ahead of their use, one 16-byte load per lane;
+//   StitchTile    - the TK activation rows named by those indices are loaded
+//                   (16 bytes per lane, coalesced along N) PD steps ahead into
+//                   registers, then written to the wavefront's private LDS
+//                   tile; the weight tile is one 16-byte load per lane from
+//                   the packed array, already in operand order;
+//   WarpMMA       - the activation tile is read back transposed
+//                   (ds_read_b64_tr_b16) as the first matrix-core operand and
+//                   multiplied with the weight operand, fp32 accumulation;
+//   ReorderedWriteBack - accumulators go through LDS so that every stored
+//                   row leaves as full 16-byte-per-lane row segments, to the
+//                   row named by row_indices.
+//
+// The product is computed as (X^T tile) x (W^T tile), i.e. the instruction's
+// row dimension runs over output columns n and its column dimension over the
+// group's rows: each lane then holds 4 consecutive n of one row, which packs
+// into one 8-byte LDS write in the epilogue.
+//
+// Operand and accumulator lane maps (checked on hardware):
+//   v_mfma_f32_32x32x16_f16  A: lane l = row l%32, k = 8*(l/32)+e
+//                            B: lane l = col l%32, k = 8*(l/32)+e
+//                            D: lane l, reg r = row 8*(r/4)+4*(l/32)+r%4, col l%32
+//   v_mfma_f32_16x16x32_f16  A: lane l = row l%16, k = 8*(l/16)+e; B alike;
+//                            D: lane l, reg r = row 4*(l/16)+r, col l%16
+//   ds_read_b64_tr_b16: inside each block of 16 lanes, result element e of
+//     lane i is element i%4 of the 8 bytes addressed by lane 4*e + i/4; with
+//     lanes 4q..4q+3 pointing at 16 consecutive n of row k_q, lane i ends up
+//     with column n_i of rows k_0..k_3.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "shflbw_internal.h"
+
+namespace shflbw {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+
+// Orders LDS traffic between the lanes of one wavefront.  The hardware runs a
+// wavefront's LDS instructions in order; this only stops the compiler from
+// moving accesses across the point.
+#define SHFLBW_WAVE_LDS_SYNC()                                   \
+    do {                                                         \
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   \
+        __builtin_amdgcn_wave_barrier();                         \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");   \
+    } while (0)
+
+struct PackedView {
+    const int32_t* row_indices;
+    const int32_t* step_ptr;
+    const int32_t* col_idx;
+    const half8* values;  // 16-byte units
+    int G;
+};
+
+// ---------------------------------------------------------------- geometry
+// A geometry answers two questions: which 8 activation values sit at
+// (reduction index k, output columns n..n+7), and where do output values
+// (original row, columns n..n+cnt-1) go.
+
+// Linear layer: X[K][N] and Y[M][N] row-major.  ALIGNED: N, ldx, ldy are
+// multiples of 8 and both bases are 16-byte aligned.
+template <bool ALIGNED>
+struct GeomLinear {
+    const _Float16* X;
+    void* Y;
+    long ldx, ldy, N;
+
+    __device__ __forceinline__ void init(long) {}
+
+    __device__ __forceinline__ half8 load8(int col, long n) const
+    {
+        half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (col < 0) return v;
+        const _Float16* p = X + (long)col * ldx + n;
+        if (ALIGNED) {
+            if (n < N) v = *reinterpret_cast<const half8*>(p);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (n + e < N) v[e] = p[e];
+        }
+        return v;
+    }
+
+    template <typename OutT, int CNT>
+    __device__ __forceinline__ void store(int row, long n, const OutT* vals) const
+    {
+        OutT* p = static_cast<OutT*>(Y) + (long)row * ldy + n;
+        if (ALIGNED) {
+            if (n < N) {
+                typedef OutT vec_t __attribute__((ext_vector_type(CNT)));
+                vec_t v;
+#pragma unroll
+                for (int e = 0; e < CNT; ++e) v[e] = vals[e];
+                *reinterpret_cast<vec_t*>(p) = v;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < CNT; ++e)
+                if (n + e < N) p[e] = vals[e];
+        }
+    }
+};
+
+// Convolution as implicit GEMM (Section 4.1): k = (c*R + r)*S + s, and
+// n = (b*Ho + y)*Wo + x for NCHW or n = (y*Wo + x)*B + b for CHWN.  This is
+// the general element-wise form; the unfolded matrix never exists in memory.
+struct GeomConv {
+    const _Float16* in;
+    void* out;
+    int B, Cin, H, W, Cout, R, S, sh, sw, ph, pw, Ho, Wo;
+    int chwn;
+    long N;
+    // per-lane decode of the 8 output positions this lane gathers for:
+    // base[e] = offset of the window origin (may be negative), yx[e] = packed
+    // (iy0, ix0) window origin; valid bit e of `live` = position exists
+    int base[8];
+    int yx[8];
+    int live;
+
+    __device__ __forceinline__ void split_n(long n, int& b, int& y, int& x) const
+    {
+        int q;
+        if (chwn) {
+            b = (int)(n % B);
+            q = (int)(n / B);
+        } else {
+            q = (int)(n % ((long)Ho * Wo));
+            b = (int)(n / ((long)Ho * Wo));
+        }
+        y = q / Wo;
+        x = q % Wo;
+    }
+
+    __device__ __forceinline__ void init(long n)
+    {
+        live = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            base[e] = 0;
+            yx[e] = 0;
+            if (n + e >= N) continue;
+            int b, y, x;
+            split_n(n + e, b, y, x);
+            const int iy0 = y * sh - ph, ix0 = x * sw - pw;
+            yx[e] = (iy0 << 16) | (ix0 & 0xffff);
+            base[e] = chwn ? (iy0 * W + ix0) * B + b : (b * Cin * H + iy0) * W + ix0;
+            live |= 1 << e;
+        }
+    }
+
+    __device__ __forceinline__ half8 load8(int col, long) const
+    {
+        half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (col < 0) return v;
+        const int c = col / (R * S);
+        const int rs = col - c * (R * S);
+        const int r = rs / S, s = rs - r * S;
+        const int koff = ((c * H + r) * W + s) * (chwn ? B : 1);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int iy = (yx[e] >> 16) + r, ix = (int)(short)(yx[e] & 0xffff) + s;
+            const bool ok = ((live >> e) & 1) && iy >= 0 && iy < H && ix >= 0 && ix < W;
+            if (ok) v[e] = in[(long)base[e] + koff];
+        }
+        return v;
+    }
+
+    template <typename OutT, int CNT>
+    __device__ __forceinline__ void store(int row, long n, const OutT* vals) const
+    {
+        OutT* o = static_cast<OutT*>(out);
+#pragma unroll
+        for (int e = 0; e < CNT; ++e) {
+            if (n + e >= N) break;
+            int b, y, x;
+            split_n(n + e, b, y, x);
+            const long idx = chwn ? (((long)row * Ho + y) * Wo + x) * B + b
+                                  : (((long)b * Cout + row) * Ho + y) * Wo + x;
+            o[idx] = vals[e];
+        }
+    }
+};
+
+// ---------------------------------------------------------------- kernel
+template <int V, int WN>
+struct GatherShape {
+    static constexpr bool SMALL = (V == 16);          // 16x16x32 instruction
+    static constexpr int TK = SMALL ? 32 : 16;        // columns per k-step
+    static constexpr int RB = SMALL ? 1 : V / 32;     // row blocks per group
+    static constexpr int TILE_N = SMALL ? 16 : 32;    // output columns per instruction
+    static constexpr int NT = WN / TILE_N;
+    static constexpr int LPR = WN / 8;                // lanes per activation row (16 B each)
+    static constexpr int RPI = 64 / LPR;              // rows per load instruction
+    static constexpr int NLD = TK / RPI;              // loads per lane per k-step
+    static constexpr int PITCH = WN + 8;              // LDS row pitch in binary16
+    static constexpr int STAGE = TK * PITCH;          // binary16 per staged tile
+    static constexpr int ROWS_E = SMALL ? 16 : 32;    // rows per epilogue pass
+    static constexpr int EPI = ROWS_E * PITCH;        // binary16 needed by one epilogue pass
+    static constexpr int REGION = (2 * STAGE > EPI) ? 2 * STAGE : EPI;
+};
+
+template <int V, int WN, int WAVES, int PD, typename OutT, class Geom>
+__global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A, Geom geom,
+                                                                  int n_tiles)
+{
+    using S = GatherShape<V, WN>;
+    constexpr int TK = S::TK, RB = S::RB, NT = S::NT, LPR = S::LPR, NLD = S::NLD;
+    constexpr int PITCH = S::PITCH;
+    __shared__ __attribute__((aligned(16))) _Float16 smem[WAVES * S::REGION];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tile = blockIdx.x * WAVES + wave;
+    if (tile >= n_tiles) return;  // whole wavefront leaves; no workgroup barrier is used
+    const int g = blockIdx.y;
+    const long n0 = (long)tile * WN;
+    _Float16* my = smem + wave * S::REGION;
+
+    const int sbeg = A.step_ptr[g];
+    const int nsteps = A.step_ptr[g + 1] - sbeg;
+
+    // this lane's share of a staged tile: rows lrow..lrow+NLD-1, 8 columns at lcol
+    const int lrow = (lane / LPR) * NLD;
+    const int lcol = (lane % LPR) * 8;
+    const long ln = n0 + lcol;
+    geom.init(ln);
+
+    floatx16 acc32[S::SMALL ? 1 : RB][S::SMALL ? 1 : NT];
+    floatx4 acc16[S::SMALL ? NT : 1];
+    if (S::SMALL) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc16[t] = floatx4{0, 0, 0, 0};
+    } else {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc32[rb][t][r] = 0.f;
+    }
+
+    // ---- pipeline registers
+    int cols[PD][NLD];
+    half8 xr[PD][NLD];
+    half8 wr[PD][RB];
+
+    auto load_cols = [&](int step, int (&c)[NLD]) {
+        const int32_t* p = A.col_idx + (long)(sbeg + step) * TK + lrow;
+        if (NLD == 4) {
+            intx4 v = *reinterpret_cast<const intx4*>(p);
+            c[0] = v[0]; c[1] = v[1]; c[2] = v[2]; c[3] = v[3];
+        } else if (NLD == 2) {
+            intx2 v = *reinterpret_cast<const intx2*>(p);
+            c[0] = v[0]; c[1] = v[1];
+        } else {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) c[i] = p[i];
+        }
+    };
+    auto load_x = [&](const int (&c)[NLD], half8 (&x)[NLD]) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) x[i] = geom.load8(c[i], ln);
+    };
+    auto load_w = [&](int step, half8 (&w)[RB]) {
+        const half8* p = A.values + ((long)(sbeg + step) * RB) * 64 + lane;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) w[rb] = p[rb * 64];
+    };
+
+#pragma unroll
+    for (int u = 0; u < PD; ++u) {
+        if (u < nsteps) {
+            int c0[NLD];
+            load_cols(u, c0);
+            load_x(c0, xr[u]);
+            load_w(u, wr[u]);
+        }
+        if (u + PD < nsteps) load_cols(u + PD, cols[u]);
+    }
+
+    // transposed-read addresses (in binary16 units inside a staged tile)
+    // 32-wide: block b = lane/16 covers n = 16*(b%2)+0..15, k = 8*(b/2)+4h+0..3
+    // 16-wide: block b covers n = 0..15,                k = 8*b+4h+0..3
+    const int bl = lane >> 4, il = lane & 15;
+    const int tr_row = S::SMALL ? (8 * bl + (il >> 2)) : (8 * (bl >> 1) + (il >> 2));
+    const int tr_col = S::SMALL ? (4 * (il & 3)) : (16 * (bl & 1) + 4 * (il & 3));
+    const int tr_off = tr_row * PITCH + tr_col;
+
+    for (int s0 = 0; s0 < nsteps; s0 += PD) {
+#pragma unroll
+        for (int u = 0; u < PD; ++u) {
+            const int s = s0 + u;
+            if (s >= nsteps) break;
+            _Float16* buf = my + (s & 1) * S::STAGE;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i)
+                *reinterpret_cast<half8*>(buf + (lrow + i) * PITCH + lcol) = xr[u][i];
+            half8 wcur[RB];
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) wcur[rb] = wr[u][rb];
+            SHFLBW_WAVE_LDS_SYNC();
+
+            if (s + PD < nsteps) {
+                load_x(cols[u], xr[u]);
+                load_w(s + PD, wr[u]);
+            }
+            if (s + 2 * PD < nsteps) load_cols(s + 2 * PD, cols[u]);
+
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const _Float16* base = buf + tr_off + t * S::TILE_N;
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(base));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(base + 4 * PITCH));
+                half4 l4 = __builtin_bit_cast(half4, lo), h4 = __builtin_bit_cast(half4, hi);
+                half8 a = {l4[0], l4[1], l4[2], l4[3], h4[0], h4[1], h4[2], h4[3]};
+                if (S::SMALL) {
+                    acc16[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wcur[0], acc16[t], 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+                        acc32[rb][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, wcur[rb], acc32[rb][t], 0, 0, 0);
+                }
+            }
+            // no second sync: the next step writes the other buffer, and its own
+            // sync separates these reads from the writes of the step after it
+        }
+    }
+    SHFLBW_WAVE_LDS_SYNC();
+
+    // ---- reordered write-back
+    // Each pass moves ROWS_E stored rows x CW columns through LDS.  A lane
+    // holds 4 consecutive n of one row per accumulator quad.
+    constexpr int OUT_PER_16B = 16 / (int)sizeof(OutT);             // 8 (fp16) or 4 (fp32)
+    constexpr int PASSES = (int)sizeof(OutT) / 2;                   // column halves per row block
+    constexpr int CW = WN / PASSES;                                  // columns per pass
+    constexpr int EP = CW + 16 / (int)sizeof(OutT);                 // pitch in OutT units
+    static_assert(S::ROWS_E * EP * (int)sizeof(OutT) <= S::REGION * 2, "epilogue tile must fit");
+    OutT* ep = reinterpret_cast<OutT*>(my);
+    constexpr int LPR_E = CW / OUT_PER_16B;                          // lanes per row at readback
+    constexpr int RPI_E = 64 / LPR_E;
+    const int erow = lane / LPR_E, echunk = lane % LPR_E;
+    const int32_t* rows_g = A.row_indices + (long)g * V;
+
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+        for (int pass = 0; pass < PASSES; ++pass) {
+            constexpr int TPP = NT / PASSES;  // instruction tiles per pass
+#pragma unroll
+            for (int tt = 0; tt < TPP; ++tt) {
+                const int t = pass * TPP + tt;
+                if (S::SMALL) {
+                    // lane: row l%16, n = 16*tt + 4*(l/16) + 0..3
+                    OutT* d = ep + (lane & 15) * EP + 16 * tt + 4 * (lane >> 4);
+                    typedef OutT vec4 __attribute__((ext_vector_type(4)));
+                    vec4 v = {(OutT)acc16[t][0], (OutT)acc16[t][1], (OutT)acc16[t][2], (OutT)acc16[t][3]};
+                    *reinterpret_cast<vec4*>(d) = v;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        OutT* d = ep + (lane & 31) * EP + 32 * tt + 8 * q + 4 * (lane >> 5);
+                        typedef OutT vec4 __attribute__((ext_vector_type(4)));
+                        vec4 v = {(OutT)acc32[rb][t][4 * q + 0], (OutT)acc32[rb][t][4 * q + 1],
+                                  (OutT)acc32[rb][t][4 * q + 2], (OutT)acc32[rb][t][4 * q + 3]};
+                        *reinterpret_cast<vec4*>(d) = v;
+                    }
+                }
+            }
+            SHFLBW_WAVE_LDS_SYNC();
+#pragma unroll
+            for (int i = 0; i < S::ROWS_E / RPI_E; ++i) {
+                const int row = i * RPI_E + erow;
+                typedef OutT vecw __attribute__((ext_vector_type(OUT_PER_16B)));
+                vecw v = *reinterpret_cast<const vecw*>(ep + row * EP + echunk * OUT_PER_16B);
+                OutT tmp[OUT_PER_16B];
+#pragma unroll
+                for (int e = 0; e < OUT_PER_16B; ++e) tmp[e] = v[e];
+                const int orig = rows_g[rb * 32 + row];
+                geom.template store<OutT, OUT_PER_16B>(orig, n0 + pass * CW + echunk * OUT_PER_16B, tmp);
+            }
+            SHFLBW_WAVE_LDS_SYNC();
+        }
+    }
+}
+
+}  // namespace shflbw

@@ -1,0 +1,51 @@
+// Internal definitions shared by the host-side compressor and the kernel
+// launchers.  Not part of the public ABI.
+#ifndef SHFLBW_INTERNAL_H
+#define SHFLBW_INTERNAL_H
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "shflbw.h"
+
+// Packed Shfl-BW matrix (offline step (a), Sections 4.1-4.3).
+//
+// Stored rows are the permuted rows; group g owns stored rows gV..gV+V-1.
+// The kept columns of a group are cut into "k-steps" of TK columns, the
+// reduction depth one matrix-core pass consumes (TK = 16 for V >= 32 on the
+// 32x32x16 instruction, TK = 32 for V = 16 on the 16x16x32 instruction).  The
+// last step of a group is padded: its column slots hold -1 and its weights
+// are zero.
+//
+// values: for each k-step, for each 32-row block rb of the group (one block
+// when V = 16), 64 lanes x 8 binary16 in the operand order of the
+// instruction:
+//   V >= 32: lane l, element e  ->  stored row 32*rb + l%32, step column 8*(l/32) + e
+//   V == 16: lane l, element e  ->  stored row l%16,         step column 8*(l/16) + e
+// so one wavefront fetches its operand with one 16-byte load per lane.
+struct shflbw_matrix {
+    int M = 0, K = 0, V = 0, G = 0, TK = 0;
+    int64_t nnz = 0;
+    std::vector<int32_t> row_indices;  // M: original row of each stored row
+    std::vector<int32_t> step_ptr;     // G+1: first k-step of each group
+    std::vector<int32_t> kcount;       // G: kept columns per group (no padding)
+    std::vector<int32_t> col_idx;      // steps*TK: ascending columns, -1 = padding
+    std::vector<uint16_t> values;      // steps*V*TK binary16 bit patterns
+
+    // device image (caller-owned buffer), byte offsets of the sections
+    size_t off_rows = 0, off_steps = 0, off_cols = 0, off_vals = 0, dev_bytes = 0;
+    void* dev_base = nullptr;
+    int dev_id = -1;
+
+    int tune_kernel = 0, tune_tile_n = 0;
+
+    int total_steps() const { return step_ptr.empty() ? 0 : step_ptr.back(); }
+};
+
+namespace shflbw {
+int fail(int status, const std::string& detail);  // records the thread-local text, returns status
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+}  // namespace shflbw
+
+#endif

@@ -1,0 +1,76 @@
+"""GPU parity of shflbw_conv2d (implicit GEMM) against the CPU oracle."""
+import numpy as np
+import pytest
+
+from oracle import c_oracle
+from paper_2203_05016_amd import binding, synth
+from conftest import assert_within_scaled_tolerance
+from gpu_util import announce
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_conv(p, out_dtype="float16", tile_n=0):
+    import torch
+    g = p.conv
+    A = binding.compress(p.W, p.mask, p.perm, p.V)
+    A.set_tuning(0, tile_n)
+    A.bind_device("cuda:0")
+    x = torch.from_numpy(g["input"]).to("cuda:0")
+    shape = (g["batch"], g["Cout"], g["Ho"], g["Wo"]) if g["layout"] == "NCHW" else \
+        (g["Cout"], g["Ho"], g["Wo"], g["batch"])
+    out = torch.full(shape, float("nan"), dtype=getattr(torch, out_dtype), device="cuda:0")
+    A.conv2d(x, g["R"], g["S"], g["stride"], g["pad"], g["layout"], out=out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def _parity(p, **kw):
+    g = p.conv
+    got = _run_conv(p, **kw)
+    want, sc = c_oracle.conv2d(p.W, p.mask, g["input"], g["R"], g["S"], g["stride"], g["pad"],
+                               g["layout"])
+    assert got.shape == want.shape
+    return assert_within_scaled_tolerance(got, want, sc, what="conv2d")
+
+
+@pytest.mark.parametrize("layout", ["NCHW", "CHWN"])
+@pytest.mark.parametrize("stride,pad,R,S", [((1, 1), (1, 1), 3, 3), ((2, 2), (1, 1), 3, 3),
+                                            ((1, 1), (0, 0), 1, 1), ((2, 1), (0, 2), 3, 2)])
+def test_conv_small_shapes(layout, stride, pad, R, S):
+    announce("conv small", layout, stride, pad, R, S)
+    p = synth.make_conv(3, 24, 9, 7, 64, R, S, 32, 0.6, seed=201, stride=stride, pad=pad,
+                        layout=layout)
+    _parity(p)
+    _parity(p, out_dtype="float32", tile_n=64)
+
+
+@pytest.mark.parametrize("V", [16, 64])
+def test_conv_other_group_sizes_integer_exact(V):
+    announce("conv integer", V)
+    p = synth.make_conv(2, 16, 7, 7, 2 * V, 3, 3, V, 0.75, seed=202, pad=(1, 1), integer=True)
+    g = p.conv
+    got = _run_conv(p, out_dtype="float32")
+    want, _ = c_oracle.conv2d(p.W, p.mask, g["input"], 3, 3, (1, 1), (1, 1))
+    assert np.array_equal(got.astype(np.float64), want)
+
+
+def test_conv_1x1_equals_spmm_path_bitwise():
+    """1x1, stride 1, no padding, CHWN: the implicit GEMM is exactly the
+    linear-layer product on the reshaped input."""
+    import torch
+    announce("conv 1x1 vs spmm")
+    p = synth.make_conv(8, 48, 5, 5, 64, 1, 1, 32, 0.5, seed=203, layout="CHWN")
+    got = _run_conv(p)
+    A = binding.compress(p.W, p.mask, p.perm, 32).bind_device("cuda:0")
+    X = torch.from_numpy(p.conv["input"].reshape(48, 5 * 5 * 8)).to("cuda:0")
+    Y = A.spmm(X)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.reshape(64, 200).view(np.uint16), Y.cpu().numpy().view(np.uint16))
+
+
+def test_config4_resnet_conv_full():
+    """Config 4 at full size (32x256x14x14, 3x3, pad 1, V=32, 75 %)."""
+    announce("config4")
+    p = synth.config(3)
+    _parity(p)

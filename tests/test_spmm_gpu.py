@@ -1,0 +1,151 @@
+"""GPU parity of shflbw_spmm against the CPU oracle, element by element, on
+seeded inputs.  Bound: |Y - Y_ref| <= 2^-10 * (|W.mask| |X|) per element
+(fp16 inputs, fp32 accumulation); bit-exact where small-integer inputs make
+the result unique."""
+import numpy as np
+import pytest
+
+from oracle import c_oracle
+from paper_2203_05016_amd import synth
+from conftest import assert_within_scaled_tolerance
+from gpu_util import announce, run_spmm
+
+pytestmark = pytest.mark.gpu
+
+
+def _parity(p, **kw):
+    Y = run_spmm(p, **kw)
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    return assert_within_scaled_tolerance(Y, Yr, S, what="spmm")
+
+
+@pytest.mark.parametrize("out_dtype", ["float16", "float32"])
+@pytest.mark.parametrize("tile_n", [64, 128])
+def test_config1_tiny(out_dtype, tile_n):
+    announce("config1", out_dtype, tile_n)
+    _parity(synth.config(0), out_dtype=out_dtype, tile_n=tile_n)
+
+
+@pytest.mark.parametrize("V", [16, 32, 64, 128])
+@pytest.mark.parametrize("tile_n", [64, 128])
+def test_integer_inputs_bit_exact(V, tile_n):
+    """Small integers: every product and partial sum is exact in fp32, so the
+    GPU must reproduce the oracle bit for bit (also after fp16 rounding of
+    the output, since |Y| stays below 2048)."""
+    announce("integer", V, tile_n)
+    p = synth.make_spmm(2 * V, 192, 200, V, 0.75, seed=31 + V, integer=True)
+    Yr, _ = c_oracle.spmm(p.W, p.mask, p.X)
+    assert np.abs(Yr).max() < 2048
+    for dt in ("float16", "float32"):
+        Y = run_spmm(p, out_dtype=dt, tile_n=tile_n)
+        assert np.array_equal(Y.astype(np.float64), Yr), dt
+
+
+@pytest.mark.parametrize("V,sp", [(16, 0.5), (16, 0.9), (32, 0.5), (32, 0.9), (64, 0.75),
+                                  (64, 0.9), (128, 0.75)])
+def test_multi_tile_ragged_tail(V, sp):
+    """Several N tiles with a ragged tail (N = 8*59), kept counts that are not
+    a multiple of the k-step, non-trivial permutation."""
+    announce("ragged-tail", V, sp)
+    p = synth.make_spmm(4 * V, 333, 472, V, sp, seed=41 + V)
+    _parity(p)
+    _parity(p, out_dtype="float32", tile_n=64)
+
+
+def test_variable_kept_counts_and_empty_groups():
+    announce("ragged groups")
+    p = synth.make_spmm(8 * 32, 300, 264, 32, 0.6, seed=51, ragged=True)
+    rows = p.perm[32:64]
+    p.mask[rows] = 0
+    p.cols[1] = np.zeros((0,), dtype=np.int64)
+    Y = run_spmm(p)
+    assert np.all(Y[rows] == 0)
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    assert_within_scaled_tolerance(Y, Yr, S, what="ragged groups")
+
+
+def test_all_groups_empty_writes_zeros():
+    announce("all empty")
+    p = synth.make_spmm(64, 40, 72, 32, 0.5, seed=52)
+    p.mask[:] = 0
+    Y = run_spmm(p)
+    assert Y.shape == (64, 72) and np.all(Y == 0)
+
+
+@pytest.mark.parametrize("N", [1, 7, 9, 130])
+def test_unaligned_n_takes_general_path(N):
+    announce("unaligned N", N)
+    p = synth.make_spmm(64, 100, N, 32, 0.5, seed=60 + N)
+    _parity(p)
+    _parity(p, out_dtype="float32")
+
+
+def test_leading_dimensions_and_misaligned_bases():
+    announce("ld / offset")
+    p = synth.make_spmm(64, 100, 136, 32, 0.5, seed=70)
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    for pad_ld, offset in ((8, 0), (3, 0), (0, 1), (8, 8)):
+        Y = run_spmm(p, pad_ld=pad_ld, offset=offset)
+        assert_within_scaled_tolerance(Y, Yr, S, what="ld=%d off=%d" % (pad_ld, offset))
+
+
+def test_dense_identity_is_gemm():
+    """Sparsity 0 with the identity permutation: the kernel is a dense GEMM."""
+    announce("dense identity")
+    p = synth.make_spmm(128, 256, 136, 32, 0.0, seed=80, identity_perm=True)
+    Y = run_spmm(p, out_dtype="float32")
+    want = p.W.astype(np.float64) @ p.X.astype(np.float64)
+    S = np.abs(p.W.astype(np.float64)) @ np.abs(p.X.astype(np.float64))
+    assert_within_scaled_tolerance(Y, want, S, what="dense")
+
+
+def test_permutation_invariant_bitwise():
+    """Shuffling the rows of W (and composing the permutation) gives the
+    packed arrays of the same groups, so Y[q] must match bit for bit."""
+    announce("perm invariant")
+    p = synth.make_spmm(128, 200, 136, 32, 0.75, seed=81)
+    Y = run_spmm(p)
+    q = np.random.Generator(np.random.PCG64(5)).permutation(128)
+    inv = np.empty(128, dtype=np.int64)
+    inv[q] = np.arange(128)
+    p2 = synth.Problem(p.M, p.K, p.N, p.V, p.W[q], p.mask[q], inv[p.perm].astype(np.int32), p.X,
+                       p.cols)
+    Y2 = run_spmm(p2)
+    assert np.array_equal(Y2.view(np.uint16), Y[q].view(np.uint16))
+
+
+def test_identity_permutation_matches_shuffled_rows():
+    announce("identity perm")
+    p = synth.make_spmm(128, 200, 136, 32, 0.75, seed=82, identity_perm=True)
+    _parity(p)
+
+
+def test_repeat_runs_are_bitwise_identical():
+    announce("determinism")
+    p = synth.config(0)
+    a = run_spmm(p)
+    b = run_spmm(p)
+    assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
+def test_large_magnitudes_and_signed_zero():
+    announce("magnitudes")
+    p = synth.make_spmm(64, 128, 72, 32, 0.5, seed=83)
+    p.W[:] = (p.W.astype(np.float32) * 30).astype(np.float16)
+    X = (p.X.astype(np.float32) * 2.0 ** -12).astype(np.float16)   # subnormal-range products
+    Y = run_spmm(p, X=X, out_dtype="float32")
+    Yr, S = c_oracle.spmm(p.W, p.mask, X)
+    assert_within_scaled_tolerance(Y, Yr, S, what="magnitudes")
+
+
+def test_config3_attention_projection_sampled():
+    """Config 3 at V=32, 75 %: full launch on the GPU, oracle on a column
+    sample (every row, 96 sampled columns incl. both ends)."""
+    announce("config3 V=32 75%")
+    p = synth.config(2, variant=3 * 1 + 1)
+    Y = run_spmm(p)
+    rng = np.random.Generator(np.random.PCG64(3))
+    cols = np.unique(np.concatenate([[0, p.N - 1], rng.choice(p.N, 94, replace=False)]))
+    Xs = np.ascontiguousarray(p.X[:, cols])
+    Yr, S = c_oracle.spmm(p.W, p.mask, Xs)
+    assert_within_scaled_tolerance(Y[:, cols], Yr, S, what="config3 sample")
