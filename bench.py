@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the Shfl-BW hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--all] [--no-cpu]
+
+A step is one pass of the whole hot path (metadata prefetch, stitched tile
+loads, matrix-core product, reordered write-back: one shflbw_spmm launch)
+over one batch of synthetic input.  Headline workload: the Transformer-big
+FFN layer, W 4096x1024 fp16, V=32, 75 % sparsity, X 1024x8192 fp16, with all
+operands resident in HBM before the timed region.  Successive steps rotate
+through enough (X, Y) buffer pairs that no activation or output byte
+survives in the 256 MB last-level cache between two uses ("cold"); the packed
+weights (2 MB) are the same every step, as in inference.
+
+Prints ONE JSON line.  value = useful TFLOP/s = 2*nnz*N / t.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_F16_PEAK = 2.5166e15      # 256 CU x 4096 FLOP/clk x 2.4 GHz
+HBM_PEAK = 8.0e12
+PAPER_CONTEXT = "paper: up to 1.81x/4.18x/1.90x over cuBLAS dense at 75% on V100/T4/A100 (context only)"
+
+
+def algorithmic_bytes(M, K, N, nnz, V, out_bytes=2):
+    """Bytes the method itself must move once: packed values, column and row
+    indices, X, Y."""
+    kept_cols = nnz // V
+    return 2 * nnz + 4 * kept_cols + 4 * M + 2 * K * N + out_bytes * M * N
+
+
+class Case:
+    """One packed matrix on the device plus rotating activation/output pairs."""
+
+    def __init__(self, p, rotate, out_dtype="float16", tile_n=0):
+        import torch
+        from paper_2203_05016_amd import binding
+        self.p = p
+        self.A = binding.compress(p.W, p.mask, p.perm, p.V)
+        self.A.set_tuning(0, tile_n)
+        self.A.bind_device("cuda:0")
+        self.info = self.A.info()
+        x0 = torch.from_numpy(p.X).to("cuda:0")
+        self.X = [x0] + [x0.clone() for _ in range(rotate - 1)]
+        dt = getattr(torch, out_dtype)
+        self.Y = [torch.empty((p.M, p.N), dtype=dt, device="cuda:0") for _ in range(rotate)]
+        self.out_bytes = 2 if out_dtype == "float16" else 4
+        self.i = 0
+
+    def step(self):
+        j = self.i % len(self.X)
+        self.A.spmm(self.X[j], self.Y[j])
+        self.i += 1
+
+    def flop(self):
+        return 2.0 * self.info["nnz"] * self.p.N
+
+    def bytes(self):
+        return algorithmic_bytes(self.p.M, self.p.K, self.p.N, self.info["nnz"], self.p.V,
+                                 self.out_bytes)
+
+
+def time_steps(fn, steps, warmup):
+    """Average milliseconds per call of fn over `steps` calls, HIP events on
+    the stream the kernels are launched on (torch's current stream)."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def rotation_for(p, out_bytes=2, cache=256 << 20):
+    per = 2 * p.K * p.N + out_bytes * p.M * p.N
+    return max(2, min(8, -(-2 * cache // per)))
+
+
+def measure_spmm(p, steps, warmup, cold=True, **kw):
+    import torch
+    rot = rotation_for(p) if cold else 1
+    c = Case(p, rot, **kw)
+    ms = time_steps(c.step, steps, warmup)
+    r = dict(ms=ms, tflops=c.flop() / (ms * 1e-3) / 1e12, gbps=c.bytes() / (ms * 1e-3) / 1e9,
+             nnz=c.info["nnz"], sparsity=c.info["sparsity"], bytes=c.bytes(), flop=c.flop(),
+             rotate=rot)
+    del c
+    torch.cuda.empty_cache()
+    return r
+
+
+def measure_conv(p, steps, warmup):
+    import torch
+    from paper_2203_05016_amd import binding
+    g = p.conv
+    A = binding.compress(p.W, p.mask, p.perm, p.V).bind_device("cuda:0")
+    x = torch.from_numpy(g["input"]).to("cuda:0")
+    out = torch.empty((g["batch"], g["Cout"], g["Ho"], g["Wo"]) if g["layout"] == "NCHW" else
+                      (g["Cout"], g["Ho"], g["Wo"], g["batch"]), dtype=torch.float16, device="cuda:0")
+    fn = lambda: A.conv2d(x, g["R"], g["S"], g["stride"], g["pad"], g["layout"], out=out)
+    ms = time_steps(fn, steps, warmup)
+    flop = 2.0 * A.info()["nnz"] * p.N
+    return dict(ms=ms, tflops=flop / (ms * 1e-3) / 1e12, flop=flop)
+
+
+def cpu_baseline(p):
+    """The oracle as it stands, on the host cores, on the full headline
+    workload (values only, no tolerance scale), best of two runs."""
+    from oracle import c_oracle
+    best = None
+    for _ in range(2):
+        t = time.perf_counter()
+        c_oracle.spmm(p.W, p.mask, p.X, want_scale=False)
+        dt = time.perf_counter() - t
+        best = dt if best is None else min(best, dt)
+    flop = 2.0 * p.nnz * p.N
+    return dict(value=flop / best / 1e12, unit="TFLOP/s", cores=c_oracle.num_threads(),
+                kind="oracle", sample="full workload (4096x1024 by 1024x8192, 75%% sparse), "
+                "best of 2 runs, %.2f s each" % best, seconds=best)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--all", action="store_true", help="also run the other configs (extra JSON file)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-baseline leg")
+    ap.add_argument("--tile-n", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards over N "
+              "without any exchange, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2203_05016_amd import synth
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    p = synth.config(1)
+    main_r = measure_spmm(p, args.steps, args.warmup, cold=True, tile_n=args.tile_n)
+    warm_r = measure_spmm(p, args.steps, args.warmup, cold=False, tile_n=args.tile_n)
+    dense_p = synth.config(1, sparsity=0.0)
+    dense_r = measure_spmm(dense_p, max(10, args.steps // 4), max(3, args.warmup // 4), cold=True,
+                           tile_n=args.tile_n)
+    ident_p = synth.config(1, identity_perm=True)
+    ident_r = measure_spmm(ident_p, args.steps, args.warmup, cold=True, tile_n=args.tile_n)
+    conv_r = measure_conv(synth.config(3), args.steps, args.warmup)
+
+    cpu = None if args.no_cpu else cpu_baseline(p)
+
+    achieved = main_r["bytes"] / (main_r["ms"] * 1e-3)
+    out = {
+        "metric": "useful TFLOP/s (2*nnz*N/s), Shfl-BW SpMM at 75% sparsity, V=32",
+        "value": main_r["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": main_r["ms"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "configs[1]: Transformer-big FFN SpMM, W 4096x1024 fp16, V=32, "
+                               "75% sparsity, X 1024x8192 fp16, Y fp16, cold operands",
+                   "M": p.M, "K": p.K, "N": p.N, "V": p.V, "nnz": main_r["nnz"],
+                   "rotating_buffer_pairs": main_r["rotate"]},
+        "roofline": {"bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": None,
+                     "algorithmic_bytes_per_launch": main_r["bytes"],
+                     "kernel": "shflbw_gather_kernel<32,...>"},
+        "mfma_peak_frac_useful": main_r["tflops"] * 1e12 / MFMA_F16_PEAK,
+        "speedup_vs_own_dense": dense_r["ms"] / main_r["ms"],
+        "dense_run": {"ms": dense_r["ms"], "tflops": dense_r["tflops"],
+                      "mfma_peak_frac": dense_r["tflops"] * 1e12 / MFMA_F16_PEAK},
+        "warm_cache": {"ms": warm_r["ms"], "tflops": warm_r["tflops"]},
+        "identity_perm": {"ms": ident_r["ms"], "shuffled_over_identity": main_r["ms"] / ident_r["ms"]},
+        "conv2d_config4": conv_r,
+        "cpu_baseline": cpu,
+        "context": PAPER_CONTEXT,
+    }
+    if args.all:
+        extra = {}
+        for variant in range(9):
+            q = synth.config(2, variant=variant)
+            r = measure_spmm(q, args.steps, args.warmup, cold=True)
+            d = measure_spmm(synth.config(2, variant=variant, sparsity=0.0), args.steps // 2 or 1,
+                             args.warmup, cold=True)
+            extra["config3_V%d_s%.2f" % (q.V, r["sparsity"])] = dict(r, dense_ms=d["ms"],
+                                                                    speedup=d["ms"] / r["ms"])
+        for variant in (3, 2, 1, 0):
+            q = synth.config(4, variant=variant)
+            r = measure_spmm(q, 10, 2, cold=True)
+            extra["config5_s%.3f" % r["sparsity"]] = r
+            del q
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_all.json"), "w") as f:
+            json.dump(extra, f, indent=1)
+        out["extra_file"] = "gpurun_out/bench_all.json"
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
