@@ -113,8 +113,10 @@ size_t shflbw_device_bytes(const shflbw_matrix* A);
 int shflbw_bind_device(shflbw_matrix* A, void* dev_buf, void* stream);
 
 /* Kernel selection, for measurement.  kernel: 0 = automatic, 1 = per-wave
- * gather kernel.  tile_n: 0 = automatic, else the number of output columns
- * one wavefront owns (64 or 128). */
+ * gather kernel, 2 = shared-slab kernel (shflbw_spmm then fails with
+ * SHFLBW_ERR_BAD_OPTION when the matrix or the operands do not allow it).
+ * tile_n: 0 = automatic, else the number of output columns one wavefront of
+ * the gather kernel owns (64 or 128). */
 int shflbw_set_tuning(shflbw_matrix* A, int kernel, int tile_n);
 
 /*

@@ -6,6 +6,7 @@
 #include <string>
 
 #include "gather_kernel.hip"
+#include "slab_kernel.hip"
 #include "shflbw_internal.h"
 
 namespace shflbw {
@@ -26,6 +27,41 @@ PackedView view_of(const shflbw_matrix* A)
     v.values = reinterpret_cast<const half8*>(b + A->off_vals);
     v.G = A->G;
     return v;
+}
+
+template <int V, int GW, typename OutT>
+int launch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long ldy, long N,
+                hipStream_t stream)
+{
+    SlabArgs a;
+    a.A = view_of(A);
+    a.iter_ptr = reinterpret_cast<const int32_t*>(static_cast<const char*>(A->dev_base) + A->off_iter);
+    a.X = static_cast<const _Float16*>(X);
+    a.Y = Y;
+    a.ldx = ldx; a.ldy = ldy; a.N = N;
+    a.K = A->K; a.C = A->slab_chunks;
+    const long n_tiles = (N + SLAB_TN - 1) / SLAB_TN;
+    a.n_tiles = (int)n_tiles;
+    a.gblocks = (A->G + GW - 1) / GW;
+    const long wgs = ((n_tiles + 7) / 8) * 8 * a.gblocks;
+    if (wgs > 0x7fffffffL) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
+    hipLaunchKernelGGL((shflbw_slab_kernel<V, GW, OutT>), dim3((unsigned)wgs), dim3(64 * GW), 0,
+                       stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return SHFLBW_OK;
+}
+
+template <typename OutT>
+int dispatch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long ldy, long N,
+                  hipStream_t stream)
+{
+    switch (A->V) {
+        case 16: return launch_slab<16, 16, OutT>(A, X, ldx, Y, ldy, N, stream);
+        case 32: return launch_slab<32, 16, OutT>(A, X, ldx, Y, ldy, N, stream);
+        case 64: return launch_slab<64, 8, OutT>(A, X, ldx, Y, ldy, N, stream);
+    }
+    return fail(SHFLBW_ERR_BAD_OPTION, "the slab kernel supports V = 16, 32, 64");
 }
 
 template <int V, int WN, typename OutT, class Geom>
@@ -96,6 +132,7 @@ int shflbw_bind_device(shflbw_matrix* A, void* dev_buf, void* stream)
     const Part parts[] = {
         {A->off_rows, A->row_indices.data(), A->row_indices.size() * sizeof(int32_t)},
         {A->off_steps, A->step_ptr.data(), A->step_ptr.size() * sizeof(int32_t)},
+        {A->off_iter, A->iter_ptr.data(), A->iter_ptr.size() * sizeof(int32_t)},
         {A->off_cols, A->col_idx.data(), A->col_idx.size() * sizeof(int32_t)},
         {A->off_vals, A->values.data(), A->values.size() * sizeof(uint16_t)},
     };
@@ -128,6 +165,13 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
     const bool aligned = (N % 8 == 0) && (ldx % 8 == 0) && (ldy % 8 == 0) &&
                          (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
+    const bool slab_possible = aligned && A->slab_ok && A->V <= 64;
+    if (A->tune_kernel == 2 && !slab_possible)
+        return fail(SHFLBW_ERR_BAD_OPTION, "slab kernel needs the windowed layout, V <= 64 and aligned operands");
+    if (A->tune_kernel == 2) {
+        if (ydtype == SHFLBW_F16) return dispatch_slab<_Float16>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);
+        return dispatch_slab<float>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);
+    }
     if (aligned) {
         GeomLinear<true> g{static_cast<const _Float16*>(X), Y, (long)ldx, (long)ldy, (long)N};
         return dispatch_out(A, g, (long)N, ydtype, st);

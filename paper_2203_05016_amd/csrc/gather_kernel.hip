@@ -31,6 +31,7 @@
 //     lane i is element i%4 of the 8 bytes addressed by lane 4*e + i/4; with
 //     lanes 4q..4q+3 pointing at 16 consecutive n of row k_q, lane i ends up
 //     with column n_i of rows k_0..k_3.
+#pragma once
 #include <hip/hip_runtime.h>
 
 #include <cstdint>

@@ -15,8 +15,16 @@
 // The kept columns of a group are cut into "k-steps" of TK columns, the
 // reduction depth one matrix-core pass consumes (TK = 16 for V >= 32 on the
 // 32x32x16 instruction, TK = 32 for V = 16 on the 16x16x32 instruction).  The
-// last step of a group is padded: its column slots hold -1 and its weights
+// steps are padded where needed: padded column slots hold -1 and their weights
 // are zero.
+//
+// Two step layouts exist.  Plain: consecutive runs of TK kept columns; only a
+// group's last step is padded.  Windowed (slab_ok): the columns are seen as
+// chunks of SLAB_KC consecutive indices and a step never spans more than two
+// adjacent chunks, so that a kernel which streams X through LDS chunk by
+// chunk finds all rows of a step resident at once; a step whose columns
+// would reach a third chunk is cut short and padded.  iter_ptr then tells,
+// per group, how many steps have their last column in a chunk below c.
 //
 // values: for each k-step, for each 32-row block rb of the group (one block
 // when V = 16), 64 lanes x 8 binary16 in the operand order of the
@@ -31,10 +39,13 @@ struct shflbw_matrix {
     std::vector<int32_t> step_ptr;     // G+1: first k-step of each group
     std::vector<int32_t> kcount;       // G: kept columns per group (no padding)
     std::vector<int32_t> col_idx;      // steps*TK: ascending columns, -1 = padding
+    bool slab_ok = false;              // windowed layout in use
+    int slab_chunks = 0;               // C = ceil(K / SLAB_KC)
+    std::vector<int32_t> iter_ptr;     // G*(C+1), only when slab_ok
     std::vector<uint16_t> values;      // steps*V*TK binary16 bit patterns
 
     // device image (caller-owned buffer), byte offsets of the sections
-    size_t off_rows = 0, off_steps = 0, off_cols = 0, off_vals = 0, dev_bytes = 0;
+    size_t off_rows = 0, off_steps = 0, off_iter = 0, off_cols = 0, off_vals = 0, dev_bytes = 0;
     void* dev_base = nullptr;
     int dev_id = -1;
 
@@ -44,6 +55,7 @@ struct shflbw_matrix {
 };
 
 namespace shflbw {
+constexpr int SLAB_KC = 128;  // rows of X per LDS chunk in the slab kernel
 int fail(int status, const std::string& detail);  // records the thread-local text, returns status
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 }  // namespace shflbw

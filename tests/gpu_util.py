@@ -11,12 +11,12 @@ def announce(*what):
     sys.stdout.flush()
 
 
-def run_spmm(p, out_dtype="float16", tile_n=0, X=None, pad_ld=0, offset=0):
+def run_spmm(p, out_dtype="float16", tile_n=0, X=None, pad_ld=0, offset=0, kernel=0):
     """Compress, bind and multiply on cuda:0; returns Y as a numpy array."""
     import torch
     from paper_2203_05016_amd import binding
     A = binding.compress(p.W, p.mask, p.perm, p.V)
-    A.set_tuning(0, tile_n)
+    A.set_tuning(kernel, tile_n)
     A.bind_device("cuda:0")
     Xh = p.X if X is None else X
     K, N = Xh.shape

@@ -1,0 +1,93 @@
+"""GPU parity of the shared-slab SpMM kernel (forced through the tuning
+switch) against the CPU oracle; same bound as the other SpMM tests."""
+import numpy as np
+import pytest
+
+from oracle import c_oracle
+from paper_2203_05016_amd import binding, synth
+from conftest import assert_within_scaled_tolerance
+from gpu_util import announce, run_spmm
+
+pytestmark = pytest.mark.gpu
+SLAB = 2
+
+
+def _parity(p, **kw):
+    Y = run_spmm(p, kernel=SLAB, **kw)
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    return assert_within_scaled_tolerance(Y, Yr, S, what="slab spmm")
+
+
+@pytest.mark.parametrize("out_dtype", ["float16", "float32"])
+def test_slab_config1_tiny(out_dtype):
+    announce("slab config1", out_dtype)
+    _parity(synth.config(0), out_dtype=out_dtype)
+
+
+@pytest.mark.parametrize("V", [16, 32, 64])
+def test_slab_integer_inputs_bit_exact(V):
+    announce("slab integer", V)
+    p = synth.make_spmm(20 * V, 400, 264, V, 0.6, seed=131 + V, integer=True)
+    Yr, _ = c_oracle.spmm(p.W, p.mask, p.X)
+    assert np.abs(Yr).max() < 2048
+    for dt in ("float16", "float32"):
+        Y = run_spmm(p, out_dtype=dt, kernel=SLAB)
+        assert np.array_equal(Y.astype(np.float64), Yr), dt
+
+
+@pytest.mark.parametrize("V,K,sp", [(16, 333, 0.5), (32, 333, 0.5), (32, 1000, 0.75),
+                                    (64, 520, 0.6), (32, 128, 0.0), (64, 384, 0.0)])
+def test_slab_multi_tile_ragged(V, K, sp):
+    """Several column tiles with a ragged tail (N = 8*59), K not a multiple of
+    the chunk, group counts that leave wavefronts of the last block idle."""
+    announce("slab ragged", V, K, sp)
+    p = synth.make_spmm(18 * V, K, 472, V, sp, seed=141 + V)
+    _parity(p)
+    _parity(p, out_dtype="float32")
+
+
+def test_slab_variable_kept_counts_and_empty_groups():
+    announce("slab ragged groups")
+    p = synth.make_spmm(20 * 32, 700, 264, 32, 0.5, seed=151, ragged=True)
+    rows = p.perm[32:64]
+    p.mask[rows] = 0
+    p.cols[1] = np.zeros((0,), dtype=np.int64)
+    Y = run_spmm(p, kernel=SLAB)
+    assert np.all(Y[rows] == 0)
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    assert_within_scaled_tolerance(Y, Yr, S, what="slab ragged groups")
+
+
+def test_slab_matches_gather_kernel_on_exact_inputs():
+    announce("slab vs gather")
+    p = synth.make_spmm(512, 640, 392, 32, 0.75, seed=152, integer=True)
+    a = run_spmm(p, kernel=1)
+    b = run_spmm(p, kernel=SLAB)
+    assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
+def test_slab_refused_when_layout_or_operands_do_not_allow_it():
+    import torch
+    announce("slab refusal")
+    p = synth.make_spmm(64, 4096, 64, 32, 0.98, seed=153)      # far too sparse for the window
+    A = binding.compress(p.W, p.mask, p.perm, 32).bind_device("cuda:0")
+    A.set_tuning(2, 0)
+    with pytest.raises(binding.ShflbwError) as e:
+        A.spmm(torch.from_numpy(p.X).to("cuda:0"))
+    assert e.value.status == -9
+    A.set_tuning(0, 0)
+    Y = A.spmm(torch.from_numpy(p.X).to("cuda:0"))
+    torch.cuda.synchronize()
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    assert_within_scaled_tolerance(Y.cpu().numpy(), Yr, S, what="fallback")
+
+
+def test_slab_config2_ffn_sampled():
+    """Headline workload at full size; oracle on a column sample."""
+    announce("slab config2")
+    p = synth.config(1)
+    Y = run_spmm(p, kernel=SLAB)
+    rng = np.random.Generator(np.random.PCG64(4))
+    cols = np.unique(np.concatenate([[0, 127, 128, p.N - 1], rng.choice(p.N, 60, replace=False)]))
+    Yr, S = c_oracle.spmm(p.W, p.mask, np.ascontiguousarray(p.X[:, cols]))
+    assert_within_scaled_tolerance(Y[:, cols], Yr, S, what="slab config2 sample")
