@@ -38,12 +38,12 @@ def algorithmic_bytes(M, K, N, nnz, V, out_bytes=2):
 class Case:
     """One packed matrix on the device plus rotating activation/output pairs."""
 
-    def __init__(self, p, rotate, out_dtype="float16", tile_n=0):
+    def __init__(self, p, rotate, out_dtype="float16", tile_n=0, kernel=0):
         import torch
         from paper_2203_05016_amd import binding
         self.p = p
         self.A = binding.compress(p.W, p.mask, p.perm, p.V)
-        self.A.set_tuning(0, tile_n)
+        self.A.set_tuning(kernel, tile_n)
         self.A.bind_device("cuda:0")
         self.info = self.A.info()
         x0 = torch.from_numpy(p.X).to("cuda:0")
@@ -139,6 +139,7 @@ def main():
     ap.add_argument("--all", action="store_true", help="also run the other configs (extra JSON file)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-baseline leg")
     ap.add_argument("--tile-n", type=int, default=0)
+    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 gather, 2 slab")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards over N "
@@ -150,13 +151,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
     p = synth.config(1)
-    main_r = measure_spmm(p, args.steps, args.warmup, cold=True, tile_n=args.tile_n)
-    warm_r = measure_spmm(p, args.steps, args.warmup, cold=False, tile_n=args.tile_n)
+    main_r = measure_spmm(p, args.steps, args.warmup, cold=True, tile_n=args.tile_n, kernel=args.kernel)
+    warm_r = measure_spmm(p, args.steps, args.warmup, cold=False, tile_n=args.tile_n, kernel=args.kernel)
     dense_p = synth.config(1, sparsity=0.0)
     dense_r = measure_spmm(dense_p, max(10, args.steps // 4), max(3, args.warmup // 4), cold=True,
-                           tile_n=args.tile_n)
+                           tile_n=args.tile_n, kernel=args.kernel)
     ident_p = synth.config(1, identity_perm=True)
-    ident_r = measure_spmm(ident_p, args.steps, args.warmup, cold=True, tile_n=args.tile_n)
+    ident_r = measure_spmm(ident_p, args.steps, args.warmup, cold=True, tile_n=args.tile_n, kernel=args.kernel)
     conv_r = measure_conv(synth.config(3), args.steps, args.warmup)
 
     cpu = None if args.no_cpu else cpu_baseline(p)

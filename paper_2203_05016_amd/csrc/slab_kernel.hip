@@ -10,15 +10,17 @@
 // k_g*128*2 bytes per group, loads are fully coalesced, and nothing is
 // written to LDS per wavefront.
 //
-// Residency.  Three LDS stages hold chunks c-1 and c (readable) while chunk
-// c+1 is being written from registers and chunk c+2, c+3 are in flight from
-// memory.  The packed matrix is cut into k-steps that never span more than
-// two adjacent chunks, and iter_ptr lists, per group, which steps have their
-// last column in chunk c: those run in iteration c.  One workgroup barrier
-// per iteration.
+// Residency.  A ring of four LDS stages: chunks c-1 and c are readable in
+// iteration c while chunks c+1 and c+2 arrive through direct global-to-LDS
+// loads (no register round trip).  The ring position of column k is
+// k mod 512, so a wavefront turns a column index into an LDS row with one
+// AND.  The packed matrix is cut into k-steps that never span more than two
+// adjacent chunks, and iter_ptr lists, per group, which steps have their last
+// column in chunk c: those run in iteration c.  One workgroup barrier per
+// iteration.
 //
-// Algorithm 1's parts: BulkLoadMeta = column indices and weight tiles of
-// the next steps prefetched into registers independent of the chunk loop;
+// Algorithm 1's parts: BulkLoadMeta = column indices and weight tile of the
+// next step prefetched into registers, independent of the chunk loop;
 // StitchTile = chunk streaming + gathered transposed reads; WarpMMA =
 // v_mfma_f32_32x32x16_f16 (16x16x32 for V = 16) with X^T as first operand;
 // ReorderedWriteBack = accumulators through LDS, 128-byte row segments stored
@@ -33,15 +35,19 @@
 namespace shflbw {
 
 constexpr int SLAB_TN = 128;                       // output columns per workgroup
-constexpr int SLAB_STAGES = 3;
+constexpr int SLAB_STAGES = 4;                     // power of two: ring row = column & (STAGES*KC-1)
 constexpr int SLAB_ROW_BYTES = SLAB_TN * 2;        // 256 B per staged row
 constexpr int SLAB_STAGE_BYTES = SLAB_KC * SLAB_ROW_BYTES;
 constexpr int SLAB_ZERO_ROW = SLAB_STAGES * SLAB_KC;  // index of the all-zero row
 constexpr int SLAB_LDS_BYTES = (SLAB_ZERO_ROW + 1) * SLAB_ROW_BYTES;
+static_assert((SLAB_STAGES & (SLAB_STAGES - 1)) == 0 && (SLAB_KC & (SLAB_KC - 1)) == 0, "ring must be a power of two");
 
-// Position of 16-byte chunk q of staged row r inside the row: rows that land
-// on the same banks get their chunks rotated against each other.
-__device__ __forceinline__ int slab_swizzle(int row, int q) { return q ^ ((row & 7) << 1); }
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(1))) const void* global_void_ptr;
+
+// s_waitcnt immediates for gfx9-family encodings: vmcnt in bits [3:0] and
+// [15:14], expcnt [6:4] and lgkmcnt [11:8] left at "do not wait".
+#define SHFLBW_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0F70)
 
 struct SlabArgs {
     PackedView A;
@@ -61,10 +67,9 @@ __global__ __launch_bounds__(64 * GW) void shflbw_slab_kernel(SlabArgs a)
     constexpr int RB = SMALL ? 1 : V / 32;
     constexpr int TILE_N = SMALL ? 16 : 32;
     constexpr int NT = SLAB_TN / TILE_N;
-    constexpr int THREADS = 64 * GW;
-    constexpr int ITEMS = SLAB_KC * 16 / THREADS;  // 16-byte pieces per thread per chunk
-    static_assert(ITEMS * THREADS == SLAB_KC * 16, "chunk must divide evenly");
-    __shared__ __attribute__((aligned(256))) char smem[SLAB_LDS_BYTES];
+    constexpr int IPW = SLAB_KC / 4 / GW;  // direct-to-LDS loads (4 rows each) per wavefront per chunk
+    static_assert(IPW * GW * 4 == SLAB_KC, "chunk must divide evenly");
+    __shared__ __attribute__((aligned(1024))) char smem[SLAB_LDS_BYTES];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -90,49 +95,33 @@ __global__ __launch_bounds__(64 * GW) void shflbw_slab_kernel(SlabArgs a)
         my_iter = a.iter_ptr + (long)g * (a.C + 1);
     }
 
-    // ---- chunk loader: thread t moves pieces t, t+THREADS, ... of a chunk;
-    // piece p is row p/16, 16-byte column chunk p%16.
-    half8 xs[2][ITEMS];
-    auto issue_chunk = [&](int c, half8 (&dst)[ITEMS]) {
+    // ---- chunk loader.  One direct-to-LDS load moves 64 x 16 bytes = 4 staged
+    // rows; lane L lands in LDS slot L of that kilobyte, so it fetches the
+    // 16-byte column chunk that the swizzle assigns to its slot.  Rows beyond K
+    // and columns beyond N are skipped: their LDS bytes are never used for a
+    // stored result.
+    const int lrow = lane >> 4;                       // row inside the 4-row piece
+    const int lpos = lane & 15;                       // slot inside the row
+    auto issue_chunk = [&](int c) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            const int p = tid + i * THREADS;
-            const int row = c * SLAB_KC + (p >> 4);
-            const long n = n0 + (p & 15) * 8;
-            half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (row < a.K && n < a.N) v = *reinterpret_cast<const half8*>(a.X + (long)row * a.ldx + n);
-            dst[i] = v;
-        }
-    };
-    auto write_chunk = [&](int c, const half8 (&src)[ITEMS]) {
-        char* stage = smem + (c % SLAB_STAGES) * SLAB_STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            const int p = tid + i * THREADS;
-            const int r = p >> 4;
-            *reinterpret_cast<half8*>(stage + r * SLAB_ROW_BYTES + (slab_swizzle(r, p & 15) << 4)) = src[i];
+        for (int i = 0; i < IPW; ++i) {
+            const int r = 4 * (wave * IPW + i) + lrow;            // row inside the chunk
+            const int q = lpos ^ ((r & 7) << 1);                  // column chunk for this slot
+            const int row = c * SLAB_KC + r;
+            const long n = n0 + q * 8;
+            char* dst = smem + (c & (SLAB_STAGES - 1)) * SLAB_STAGE_BYTES + 4 * (wave * IPW + i) * SLAB_ROW_BYTES;
+            if (row < a.K && n < a.N)
+                __builtin_amdgcn_global_load_lds((global_void_ptr)(a.X + (long)row * a.ldx + n),
+                                                 (lds_void_ptr)dst, 16, 0, 0);
         }
     };
 
-    // ---- per-step prefetch state (two register sets, picked by step parity)
-    constexpr int NC = SMALL ? 2 : 2;  // column indices a lane needs per step (one per transposed read)
-    int cols[2][NC];
-    half8 wr[2][RB];
     const int bl = lane >> 4, il = lane & 15;
     // k index of this lane's first transposed read inside a step
     const int kq = SMALL ? (8 * bl + (il >> 2)) : (8 * (bl >> 1) + (il >> 2));
     // 16-byte chunk (before the tile offset) and byte inside it that this lane reads
     const int qc = SMALL ? ((il & 3) >> 1) : (2 * (bl & 1) + ((il & 3) >> 1));
     const int qbyte = (il & 1) << 3;
-
-    auto load_meta = [&](int s, int (&c)[NC], half8 (&w)[RB]) {
-        const int32_t* p = a.A.col_idx + (long)(sbeg + s) * TK + kq;
-        c[0] = p[0];
-        c[1] = p[4];
-        const half8* q = a.A.values + ((long)(sbeg + s) * RB) * 64 + lane;
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) w[rb] = q[rb * 64];
-    };
 
     floatx16 acc32[SMALL ? 1 : RB][SMALL ? 1 : NT];
     floatx4 acc16[SMALL ? NT : 1];
@@ -148,69 +137,76 @@ __global__ __launch_bounds__(64 * GW) void shflbw_slab_kernel(SlabArgs a)
                 for (int r = 0; r < 16; ++r) acc32[rb][t][r] = 0.f;
     }
 
-    auto do_step = [&](const int (&c)[NC], const half8 (&w)[RB]) {
-        int base[2], swz[2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int row = (c[h] < 0) ? SLAB_ZERO_ROW : (c[h] % (SLAB_STAGES * SLAB_KC));
-            base[h] = row * SLAB_ROW_BYTES + qbyte;
-            swz[h] = (row & 7) << 1;
-        }
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const int q = (SMALL ? 2 * t : 4 * t) + qc;
-            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (lds_short4_ptr)(smem + base[0] + ((q ^ swz[0]) << 4)));
-            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (lds_short4_ptr)(smem + base[1] + ((q ^ swz[1]) << 4)));
-            half4 l4 = __builtin_bit_cast(half4, lo), h4 = __builtin_bit_cast(half4, hi);
-            half8 x = {l4[0], l4[1], l4[2], l4[3], h4[0], h4[1], h4[2], h4[3]};
-            if (SMALL) {
-                acc16[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x, w[0], acc16[t], 0, 0, 0);
-            } else {
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-                    acc32[rb][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x, w[rb], acc32[rb][t], 0, 0, 0);
-            }
-        }
-    };
-
     // ---- prologue
     if (tid < 16) *reinterpret_cast<half8*>(smem + SLAB_ZERO_ROW * SLAB_ROW_BYTES + tid * 16) =
         half8{0, 0, 0, 0, 0, 0, 0, 0};
     const int C = a.C;
-    {
-        half8 first[ITEMS];
-        issue_chunk(0, first);
-        if (1 < C) issue_chunk(1, xs[1]);
-        if (2 < C) issue_chunk(2, xs[0]);
-        if (0 < nsteps) load_meta(0, cols[0], wr[0]);
-        if (1 < nsteps) load_meta(1, cols[1], wr[1]);
-        write_chunk(0, first);
+    issue_chunk(0);
+    if (1 < C) issue_chunk(1);
+
+    // metadata of the next step (column indices of this lane's two transposed
+    // reads, weight operand), fetched one step ahead; the index is clamped so
+    // the loads are unconditional
+    const int last = nsteps > 0 ? nsteps - 1 : 0;
+    const int32_t* colp = a.A.col_idx + (long)sbeg * TK + kq;
+    const half8* valp = a.A.values + (long)sbeg * RB * 64 + lane;
+    int c0n = -1, c1n = -1;
+    half8 wn[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) wn[rb] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+    if (nsteps > 0) {
+        c0n = colp[0];
+        c1n = colp[4];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) wn[rb] = valp[rb * 64];
     }
+
     int s = 0;
     int it_end = have_group ? my_iter[1] : 0;
 
-    auto iteration = [&](int c, half8 (&write_set)[ITEMS], bool) {
-        __syncthreads();  // chunk c is complete; nobody still reads chunk c-2
-        if (c + 1 < C) write_chunk(c + 1, write_set);
-        if (c + 3 < C) issue_chunk(c + 3, write_set);
+    for (int c = 0; c < C; ++c) {
+        // my pieces of chunk c (issued two iterations ago) and of chunk c+1 have
+        // landed; after the barrier everybody's have, and nobody still reads
+        // chunk c-2, whose stage chunk c+2 now takes
+        SHFLBW_WAIT_VMCNT0();
+        __syncthreads();
+        if (c + 2 < C) issue_chunk(c + 2);
         const int s_end = it_end;
-        if (have_group && c + 2 <= C) it_end = my_iter[(c + 2 <= C) ? c + 2 : C];
+        if (have_group) it_end = my_iter[(c + 2 <= C) ? c + 2 : C];
         for (; s < s_end; ++s) {
-            if (s & 1) {
-                do_step(cols[1], wr[1]);
-                if (s + 2 < nsteps) load_meta(s + 2, cols[1], wr[1]);
-            } else {
-                do_step(cols[0], wr[0]);
-                if (s + 2 < nsteps) load_meta(s + 2, cols[0], wr[0]);
+            const int c0 = c0n, c1 = c1n;
+            half8 w[RB];
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) w[rb] = wn[rb];
+            {
+                const int sn = (s + 1 < nsteps) ? s + 1 : last;
+                c0n = colp[(long)sn * TK];
+                c1n = colp[(long)sn * TK + 4];
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) wn[rb] = valp[((long)sn * RB + rb) * 64];
+            }
+            const int row0 = (c0 < 0) ? SLAB_ZERO_ROW : (c0 & (SLAB_ZERO_ROW - 1));
+            const int row1 = (c1 < 0) ? SLAB_ZERO_ROW : (c1 & (SLAB_ZERO_ROW - 1));
+            const int base0 = row0 * SLAB_ROW_BYTES + qbyte, swz0 = (row0 & 7) << 1;
+            const int base1 = row1 * SLAB_ROW_BYTES + qbyte, swz1 = (row1 & 7) << 1;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int q = (SMALL ? 2 * t : 4 * t) + qc;
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (lds_short4_ptr)(smem + base0 + ((q ^ swz0) << 4)));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (lds_short4_ptr)(smem + base1 + ((q ^ swz1) << 4)));
+                half4 l4 = __builtin_bit_cast(half4, lo), h4 = __builtin_bit_cast(half4, hi);
+                half8 x = {l4[0], l4[1], l4[2], l4[3], h4[0], h4[1], h4[2], h4[3]};
+                if (SMALL) {
+                    acc16[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x, w[0], acc16[t], 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+                        acc32[rb][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x, w[rb], acc32[rb][t], 0, 0, 0);
+                }
             }
         }
-    };
-    // chunk x travels in register set x%2... chunk 1 -> xs[1], chunk 2 -> xs[0]
-    for (int c = 0; c < C; c += 2) {
-        iteration(c, xs[1], true);
-        if (c + 1 < C) iteration(c + 1, xs[0], true);
     }
     __syncthreads();  // all transposed reads done: the stages become epilogue scratch
 
