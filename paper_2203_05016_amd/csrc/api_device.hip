@@ -36,6 +36,7 @@ int launch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long l
     SlabArgs a;
     a.A = view_of(A);
     a.iter_ptr = reinterpret_cast<const int32_t*>(static_cast<const char*>(A->dev_base) + A->off_iter);
+    a.table = reinterpret_cast<const uint32_t*>(static_cast<const char*>(A->dev_base) + A->off_table);
     a.X = static_cast<const _Float16*>(X);
     a.Y = Y;
     a.ldx = ldx; a.ldy = ldy; a.N = N;
@@ -45,7 +46,7 @@ int launch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long l
     a.gblocks = (A->G + GW - 1) / GW;
     const long wgs = ((n_tiles + 7) / 8) * 8 * a.gblocks;
     if (wgs > 0x7fffffffL) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
-    hipLaunchKernelGGL((shflbw_slab_kernel<V, GW, OutT>), dim3((unsigned)wgs), dim3(64 * GW), 0,
+    hipLaunchKernelGGL((shflbw_slab_kernel<V, GW, OutT>), dim3((unsigned)wgs), dim3(64 * (GW + SLAB_LOADERS)), 0,
                        stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
@@ -57,8 +58,8 @@ int dispatch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long
                   hipStream_t stream)
 {
     switch (A->V) {
-        case 16: return launch_slab<16, 16, OutT>(A, X, ldx, Y, ldy, N, stream);
-        case 32: return launch_slab<32, 16, OutT>(A, X, ldx, Y, ldy, N, stream);
+        case 16: return launch_slab<16, 12, OutT>(A, X, ldx, Y, ldy, N, stream);
+        case 32: return launch_slab<32, 12, OutT>(A, X, ldx, Y, ldy, N, stream);
         case 64: return launch_slab<64, 8, OutT>(A, X, ldx, Y, ldy, N, stream);
     }
     return fail(SHFLBW_ERR_BAD_OPTION, "the slab kernel supports V = 16, 32, 64");
@@ -134,6 +135,7 @@ int shflbw_bind_device(shflbw_matrix* A, void* dev_buf, void* stream)
         {A->off_steps, A->step_ptr.data(), A->step_ptr.size() * sizeof(int32_t)},
         {A->off_iter, A->iter_ptr.data(), A->iter_ptr.size() * sizeof(int32_t)},
         {A->off_cols, A->col_idx.data(), A->col_idx.size() * sizeof(int32_t)},
+        {A->off_table, A->slab_table.data(), A->slab_table.size() * sizeof(uint32_t)},
         {A->off_vals, A->values.data(), A->values.size() * sizeof(uint16_t)},
     };
     for (const Part& p : parts) {

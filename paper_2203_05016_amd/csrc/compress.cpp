@@ -129,7 +129,7 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
                 size_t j = i;
                 const int first_chunk = c[i] / shflbw::SLAB_KC;
                 while (j < c.size() && j < i + (size_t)TK &&
-                       (!windowed || c[j] / shflbw::SLAB_KC <= first_chunk + 1))
+                       (!windowed || c[j] / shflbw::SLAB_KC < first_chunk + shflbw::SLAB_WINDOW))
                     ++j;
                 lens.push_back((int)(j - i));
                 i = j;
@@ -184,11 +184,30 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
             }
         }
 
+        if (A->slab_ok) {
+            // lane map of the transposed LDS read, see slab_kernel.hip
+            A->slab_table.resize(steps * 64);
+            for (size_t st = 0; st < steps; ++st)
+                for (int lane = 0; lane < 64; ++lane) {
+                    const int bl = lane >> 4, il = lane & 15;
+                    const int kq = (V == 16) ? (8 * bl + (il >> 2)) : (8 * (bl >> 1) + (il >> 2));
+                    uint32_t e = 0;
+                    for (int h = 0; h < 2; ++h) {
+                        const int k = A->col_idx[st * TK + kq + 4 * h];
+                        const uint32_t row = k < 0 ? (uint32_t)shflbw::SLAB_ZERO_ROW
+                                                   : (uint32_t)(k % shflbw::SLAB_RING_ROWS);
+                        e |= row << (16 * h);
+                    }
+                    A->slab_table[st * 64 + lane] = e;
+                }
+        }
+
         A->off_rows = 0;
         A->off_steps = shflbw::align256(A->off_rows + sizeof(int32_t) * (size_t)M);
         A->off_iter = shflbw::align256(A->off_steps + sizeof(int32_t) * (size_t)(G + 1));
         A->off_cols = shflbw::align256(A->off_iter + sizeof(int32_t) * A->iter_ptr.size());
-        A->off_vals = shflbw::align256(A->off_cols + sizeof(int32_t) * A->col_idx.size());
+        A->off_table = shflbw::align256(A->off_cols + sizeof(int32_t) * A->col_idx.size());
+        A->off_vals = shflbw::align256(A->off_table + sizeof(uint32_t) * A->slab_table.size());
         A->dev_bytes = shflbw::align256(A->off_vals + sizeof(uint16_t) * A->values.size());
         if (A->dev_bytes == 0) A->dev_bytes = 256;
 

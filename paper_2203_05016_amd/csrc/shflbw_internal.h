@@ -20,10 +20,10 @@
 //
 // Two step layouts exist.  Plain: consecutive runs of TK kept columns; only a
 // group's last step is padded.  Windowed (slab_ok): the columns are seen as
-// chunks of SLAB_KC consecutive indices and a step never spans more than two
-// adjacent chunks, so that a kernel which streams X through LDS chunk by
+// chunks of SLAB_KC consecutive indices and a step never spans more than
+// SLAB_WINDOW adjacent chunks, so that a kernel which streams X through LDS chunk by
 // chunk finds all rows of a step resident at once; a step whose columns
-// would reach a third chunk is cut short and padded.  iter_ptr then tells,
+// would reach one chunk more is cut short and padded.  iter_ptr then tells,
 // per group, how many steps have their last column in a chunk below c.
 //
 // values: for each k-step, for each 32-row block rb of the group (one block
@@ -42,10 +42,12 @@ struct shflbw_matrix {
     bool slab_ok = false;              // windowed layout in use
     int slab_chunks = 0;               // C = ceil(K / SLAB_KC)
     std::vector<int32_t> iter_ptr;     // G*(C+1), only when slab_ok
+    std::vector<uint32_t> slab_table;  // steps*64, only when slab_ok: per lane, the LDS ring rows of its
+                                       // two transposed reads of the step (low | high << 16)
     std::vector<uint16_t> values;      // steps*V*TK binary16 bit patterns
 
     // device image (caller-owned buffer), byte offsets of the sections
-    size_t off_rows = 0, off_steps = 0, off_iter = 0, off_cols = 0, off_vals = 0, dev_bytes = 0;
+    size_t off_rows = 0, off_steps = 0, off_iter = 0, off_cols = 0, off_table = 0, off_vals = 0, dev_bytes = 0;
     void* dev_base = nullptr;
     int dev_id = -1;
 
@@ -55,7 +57,11 @@ struct shflbw_matrix {
 };
 
 namespace shflbw {
-constexpr int SLAB_KC = 128;  // rows of X per LDS chunk in the slab kernel
+constexpr int SLAB_KC = 64;      // rows of X per LDS chunk in the slab kernel
+constexpr int SLAB_WINDOW = 4;   // adjacent chunks a k-step may span (readable at once)
+constexpr int SLAB_LEAD = 2;     // chunks in flight ahead of the readable window
+constexpr int SLAB_RING_ROWS = SLAB_KC * (SLAB_WINDOW + SLAB_LEAD);  // rows of X resident in LDS; row of column k = k % RING_ROWS
+constexpr int SLAB_ZERO_ROW = SLAB_RING_ROWS;                       // one extra all-zero row for padded slots
 int fail(int status, const std::string& detail);  // records the thread-local text, returns status
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 }  // namespace shflbw
