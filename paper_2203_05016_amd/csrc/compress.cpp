@@ -143,22 +143,29 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
             n_plain += plain[g].size();
             n_win += win[g].size();
         }
-        A->slab_ok = n_plain > 0 && (double)n_win <= 1.15 * (double)n_plain;
+        A->slab_ok = n_plain > 0 && (double)n_win <= 1.15 * (double)n_plain && A->slab_chunks < (1 << 14);
         A->slab_chunks = (K + shflbw::SLAB_KC - 1) / shflbw::SLAB_KC;
         const std::vector<std::vector<int>>& lens = A->slab_ok ? win : plain;
 
+        // In the windowed layout every group gets a multiple of SLAB_UNROLL steps
+        // (the slab kernel runs its steps in unrolled batches); the extra steps are
+        // empty: no columns, zero weights.
+        auto padded = [&](size_t n) {
+            return A->slab_ok ? (n + shflbw::SLAB_UNROLL - 1) / shflbw::SLAB_UNROLL * shflbw::SLAB_UNROLL : n;
+        };
         A->step_ptr.assign(G + 1, 0);
         A->kcount.resize(G);
         for (int g = 0; g < G; ++g) {
             A->kcount[g] = (int)cols[g].size();
             A->nnz += (int64_t)cols[g].size() * V;
-            A->step_ptr[g + 1] = A->step_ptr[g] + (int)lens[g].size();
+            A->step_ptr[g + 1] = A->step_ptr[g] + (int)padded(lens[g].size());
         }
         const size_t steps = (size_t)A->step_ptr[G];
         A->col_idx.assign(steps * TK, -1);
         A->values.assign(steps * (size_t)V * TK, 0);
         const int C = A->slab_chunks;
-        if (A->slab_ok) A->iter_ptr.assign((size_t)G * (C + 1), 0);
+        if (A->slab_ok) A->step_iter.assign(steps, 0);
+        (void)C;
         for (int g = 0; g < G; ++g) {
             const int32_t* rows = &A->row_indices[(size_t)g * V];
             size_t step = (size_t)A->step_ptr[g];
@@ -172,16 +179,15 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
                         dst[value_slot(V, i, j)] = Wb[(size_t)rows[i] * ldw + k];
                 }
                 if (A->slab_ok) {
-                    // this step runs in the iteration of its last column's chunk
-                    const int e = cols[g][t - 1] / shflbw::SLAB_KC;
-                    A->iter_ptr[(size_t)g * (C + 1) + e + 1] += 1;
+                    // this step runs once the chunk of its last column is resident
+                    A->step_iter[step] = cols[g][t - 1] / shflbw::SLAB_KC;
                 }
                 ++step;
             }
-            if (A->slab_ok) {
-                int32_t* ip = &A->iter_ptr[(size_t)g * (C + 1)];
-                for (int c = 0; c < C; ++c) ip[c + 1] += ip[c];
-            }
+            // empty padding steps inherit the iteration of the step before them
+            for (; step < (size_t)A->step_ptr[g + 1]; ++step)
+                if (A->slab_ok)
+                    A->step_iter[step] = step > (size_t)A->step_ptr[g] ? A->step_iter[step - 1] : 0;
         }
 
         if (A->slab_ok) {
@@ -191,12 +197,12 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
                 for (int lane = 0; lane < 64; ++lane) {
                     const int bl = lane >> 4, il = lane & 15;
                     const int kq = (V == 16) ? (8 * bl + (il >> 2)) : (8 * (bl >> 1) + (il >> 2));
-                    uint32_t e = 0;
+                    uint32_t e = (uint32_t)A->step_iter[st] << 18;
                     for (int h = 0; h < 2; ++h) {
                         const int k = A->col_idx[st * TK + kq + 4 * h];
                         const uint32_t row = k < 0 ? (uint32_t)shflbw::SLAB_ZERO_ROW
                                                    : (uint32_t)(k % shflbw::SLAB_RING_ROWS);
-                        e |= row << (16 * h);
+                        e |= row << (9 * h);
                     }
                     A->slab_table[st * 64 + lane] = e;
                 }
@@ -205,7 +211,7 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
         A->off_rows = 0;
         A->off_steps = shflbw::align256(A->off_rows + sizeof(int32_t) * (size_t)M);
         A->off_iter = shflbw::align256(A->off_steps + sizeof(int32_t) * (size_t)(G + 1));
-        A->off_cols = shflbw::align256(A->off_iter + sizeof(int32_t) * A->iter_ptr.size());
+        A->off_cols = shflbw::align256(A->off_iter);
         A->off_table = shflbw::align256(A->off_cols + sizeof(int32_t) * A->col_idx.size());
         A->off_vals = shflbw::align256(A->off_table + sizeof(uint32_t) * A->slab_table.size());
         A->dev_bytes = shflbw::align256(A->off_vals + sizeof(uint16_t) * A->values.size());

@@ -23,8 +23,13 @@
 // chunks of SLAB_KC consecutive indices and a step never spans more than
 // SLAB_WINDOW adjacent chunks, so that a kernel which streams X through LDS chunk by
 // chunk finds all rows of a step resident at once; a step whose columns
-// would reach one chunk more is cut short and padded.  iter_ptr then tells,
-// per group, how many steps have their last column in a chunk below c.
+// would reach one chunk more is cut short and padded, and every group's step
+// count is rounded up to a multiple of SLAB_UNROLL with empty steps.
+// slab_table holds, per step and lane, what the slab kernel needs to run the
+// step: bits 0-8 and 9-17 are the LDS ring rows (column mod SLAB_RING_ROWS,
+// or SLAB_ZERO_ROW for padding) of the lane's two transposed reads, bits 18-31
+// the chunk of the step's last column (the step may run once that chunk is
+// resident).
 //
 // values: for each k-step, for each 32-row block rb of the group (one block
 // when V = 16), 64 lanes x 8 binary16 in the operand order of the
@@ -41,9 +46,8 @@ struct shflbw_matrix {
     std::vector<int32_t> col_idx;      // steps*TK: ascending columns, -1 = padding
     bool slab_ok = false;              // windowed layout in use
     int slab_chunks = 0;               // C = ceil(K / SLAB_KC)
-    std::vector<int32_t> iter_ptr;     // G*(C+1), only when slab_ok
-    std::vector<uint32_t> slab_table;  // steps*64, only when slab_ok: per lane, the LDS ring rows of its
-                                       // two transposed reads of the step (low | high << 16)
+    std::vector<int32_t> step_iter;    // steps, only when slab_ok: chunk of each step's last column
+    std::vector<uint32_t> slab_table;  // steps*64, only when slab_ok (see above)
     std::vector<uint16_t> values;      // steps*V*TK binary16 bit patterns
 
     // device image (caller-owned buffer), byte offsets of the sections
@@ -57,11 +61,18 @@ struct shflbw_matrix {
 };
 
 namespace shflbw {
-constexpr int SLAB_KC = 64;      // rows of X per LDS chunk in the slab kernel
-constexpr int SLAB_WINDOW = 4;   // adjacent chunks a k-step may span (readable at once)
-constexpr int SLAB_LEAD = 2;     // chunks in flight ahead of the readable window
+#ifndef SHFLBW_SLAB_KC
+#define SHFLBW_SLAB_KC 64
+#define SHFLBW_SLAB_WINDOW 4
+#define SHFLBW_SLAB_LEAD 2
+#endif
+constexpr int SLAB_KC = SHFLBW_SLAB_KC;          // rows of X per LDS chunk in the slab kernel
+constexpr int SLAB_WINDOW = SHFLBW_SLAB_WINDOW;  // adjacent chunks a k-step may span (readable at once)
+constexpr int SLAB_LEAD = SHFLBW_SLAB_LEAD;      // chunks in flight ahead of the readable window
 constexpr int SLAB_RING_ROWS = SLAB_KC * (SLAB_WINDOW + SLAB_LEAD);  // rows of X resident in LDS; row of column k = k % RING_ROWS
 constexpr int SLAB_ZERO_ROW = SLAB_RING_ROWS;                       // one extra all-zero row for padded slots
+constexpr int SLAB_UNROLL = 4;                                      // steps per unrolled batch of the slab kernel
+static_assert(SLAB_ZERO_ROW < 512, "ring rows are stored in 9 bits");
 int fail(int status, const std::string& detail);  // records the thread-local text, returns status
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 }  // namespace shflbw

@@ -16,17 +16,26 @@
 // an exact s_waitcnt vmcnt(n); the compute wavefronts never wait on X traffic
 // and the loaders never wait on weights.
 //
-// Residency.  A ring of six 16 KB stages: in iteration c the chunks
-// c-3 .. c are readable and c+1, c+2 are in flight.  The ring row of column
-// k is k mod 384; the compressor stores it, per lane, in a table next to
-// the weights.  The packed matrix is cut into k-steps whose columns span at
-// most four adjacent chunks, and iter_ptr lists, per group, which steps have
-// their last column in chunk c: those run in iteration c.  One workgroup
-// barrier per iteration.
+// Residency and hand-over.  A ring of six 16 KB stages.  The packed matrix is
+// cut into k-steps whose columns span at most four adjacent chunks; a step
+// may run once the chunk c of its last column has landed, when chunks
+// c-3 .. c are resident.  There is no workgroup barrier in the loop.  Each
+// loader publishes in LDS how many chunks it has landed, each compute
+// wavefront the chunk of the step it is working on (it has finished every
+// step of an earlier chunk); a compute wavefront polls the former before a
+// step, a loader polls the latter only before it reuses a stage.  Wavefronts
+// therefore drift apart by up to two chunks, which is what overlaps one
+// wavefront's LDS latency with another's matrix-core time.  The polls are
+// bounded: a wavefront that does not see its condition within about a
+// million tries goes on regardless (wrong numbers instead of a hang).
 //
-// Algorithm 1's parts: BulkLoadMeta = each step's weight tile and lane table
-// brought into a per-wavefront LDS ring by direct loads three steps ahead,
-// independent of the chunk loop;
+// Per step and lane the compressor stores one table word: the LDS ring rows
+// (column mod 384) of the lane's two transposed reads and the step's chunk.
+//
+// Algorithm 1's parts: BulkLoadMeta = each step's weight tile and table word
+// fetched into registers four steps ahead (the steps of a group come in
+// batches of four, so the four register sets are compile-time choices and
+// the compiler's own wait counts are exact);
 // StitchTile = chunk streaming + gathered transposed reads; WarpMMA =
 // v_mfma_f32_32x32x16_f16 (16x16x32 for V = 16) with X^T as first operand;
 // ReorderedWriteBack = accumulators through LDS, 128-byte row segments stored
@@ -50,6 +59,8 @@ constexpr int SLAB_IPL = SLAB_KC / 4 / SLAB_LOADERS;  // direct loads (4 rows ea
 static_assert(SLAB_IPL * SLAB_LOADERS * 4 == SLAB_KC, "chunk must divide evenly");
 static_assert(SLAB_IPL * (SLAB_LEAD - 1) < 16, "vmcnt immediates below use the low four bits only");
 
+constexpr int SLAB_SPIN_LIMIT = 1 << 20;
+
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef __attribute__((address_space(3))) char* lds_char_ptr;
 typedef __attribute__((address_space(1))) const void* global_void_ptr;
@@ -58,26 +69,19 @@ typedef __attribute__((address_space(1))) const void* global_void_ptr;
 // expcnt [6:4] and lgkmcnt [11:8] left at "do not wait".
 #define SHFLBW_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
 
-// Direct global-to-LDS loads issued from inline assembly, for the compute
-// wavefronts' metadata ring: lane L's 16 (4) bytes land at lds_off + 16*L
-// (4*L).  The compiler does not know these are loads, so it neither counts
-// them in its own s_waitcnt bookkeeping nor drains them in front of unrelated
-// LDS reads; the code that issues them waits with an explicit vmcnt.
+// Direct global-to-LDS load issued from inline assembly: lane L's 16 bytes
+// land at lds_off + 16*L.  The compiler does not know this is a load, so it
+// neither counts it in its own s_waitcnt bookkeeping nor drains it in front
+// of unrelated LDS reads; the loader that issues it waits with an explicit
+// vmcnt.
 __device__ __forceinline__ void meta_dma16(const void* g, unsigned lds_off)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                  :: "s"(lds_off), "v"(g) : "memory");
 }
-__device__ __forceinline__ void meta_dma4(const void* g, unsigned lds_off)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
-                 :: "s"(lds_off), "v"(g) : "memory");
-}
-
 struct SlabArgs {
     PackedView A;
-    const int32_t* iter_ptr;  // G*(C+1)
-    const uint32_t* table;    // steps*64 lane table of LDS ring rows
+    const uint32_t* table;    // steps*64 table words (ring rows, chunk)
     const _Float16* X;
     void* Y;
     long ldx, ldy, N;
@@ -93,13 +97,12 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     constexpr int RB = SMALL ? 1 : V / 32;
     constexpr int TILE_N = SMALL ? 16 : 32;
     constexpr int NT = SLAB_TN / TILE_N;
-    // metadata ring of a compute wavefront: RING slots of (weight tile, lane table)
-    constexpr int RING = (RB == 1) ? 4 : 3;
-    constexpr int SLOT_BYTES = RB * 1024 + 256;
-    constexpr int LPS = RB + 1;                      // direct loads per step
-    constexpr int META_WAIT = LPS * (RING - 1);      // loads younger than the current step's
-    static_assert(META_WAIT < 16, "vmcnt immediate");
-    constexpr int LDS_BYTES = SLAB_X_BYTES + GW * RING * SLOT_BYTES;
+    constexpr int PD = SLAB_UNROLL;                   // register sets of prefetched metadata
+    constexpr int WAVE_BYTES = 32 * 144;              // write-back scratch of one compute wavefront
+    constexpr int SCRATCH_OFF = SLAB_X_BYTES;
+    constexpr int FLAGS_OFF = SCRATCH_OFF + GW * WAVE_BYTES;  // landed[4], progress[GW]
+    constexpr int LDS_BYTES = FLAGS_OFF + 128;
+    static_assert(SLAB_LOADERS + GW <= 32, "flag block");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
     __shared__ __attribute__((aligned(1024))) char smem[LDS_BYTES];
 
@@ -118,6 +121,21 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     const long n0 = (long)nt * SLAB_TN;
     const int C = a.C;
 
+    typedef __attribute__((address_space(3))) volatile int* lds_flag_ptr;
+    lds_flag_ptr landed = (lds_flag_ptr)(smem + FLAGS_OFF);  // per loader: chunks landed
+    lds_flag_ptr progress = landed + SLAB_LOADERS;           // per compute wavefront: iterations done
+    if (tid < 32) landed[tid] = 0;
+    if (tid >= 64 && tid < 80)  // the all-zero row
+        *reinterpret_cast<half8*>(smem + SLAB_ZERO_ROW * SLAB_ROW_BYTES + (tid - 64) * 16) =
+            half8{0, 0, 0, 0, 0, 0, 0, 0};
+    __syncthreads();
+    // true once flags[0..count) are all >= need
+    auto reached = [&](lds_flag_ptr flags, int count, int need) __attribute__((always_inline)) {
+        const int v = flags[lane & 15];
+        return __builtin_amdgcn_ballot_w64(lane < count && v < need) == 0;
+    };
+    static_assert(GW <= 16 && SLAB_LOADERS + 16 + 16 <= 32 + 4, "flag reads stay inside the flag block");
+
     if (wave >= GW) {
         // ------------------------------------------------------------ loader
         // One direct-to-LDS load moves 64 x 16 bytes = 4 staged rows; lane L
@@ -128,6 +146,7 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
         // loads per chunk is exact.
         const int lw = wave - GW;
         const int lrow = lane >> 4, lpos = lane & 15;
+        const unsigned x_off = (unsigned)(size_t)(lds_char_ptr)smem;
         auto issue_chunk = [&](int c) __attribute__((always_inline)) {
 #pragma unroll
             for (int i = 0; i < SLAB_IPL; ++i) {
@@ -138,15 +157,10 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
                 row = row < a.K ? row : a.K - 1;
                 long n = n0 + q * 8;
                 n = n < a.N ? n : n0;
-                char* dst = smem + (c % SLAB_STAGES) * SLAB_STAGE_BYTES + piece * 4 * SLAB_ROW_BYTES;
-                __builtin_amdgcn_global_load_lds((global_void_ptr)(a.X + (long)row * a.ldx + n),
-                                                 (lds_void_ptr)dst, 16, 0, 0);
+                meta_dma16(a.X + (long)row * a.ldx + n,
+                           x_off + (c % SLAB_STAGES) * SLAB_STAGE_BYTES + piece * 4 * SLAB_ROW_BYTES);
             }
         };
-        // lanes 0..15 of the first loader clear the zero row
-        if (lw == 0 && lane < 16)
-            *reinterpret_cast<half8*>(smem + SLAB_ZERO_ROW * SLAB_ROW_BYTES + lane * 16) =
-                half8{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int c = 0; c < SLAB_LEAD; ++c)
             if (c < C) issue_chunk(c);
@@ -156,32 +170,36 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
             int younger = C - 1 - c;
             younger = younger < SLAB_LEAD - 1 ? younger : SLAB_LEAD - 1;
             switch (younger) {
-                case 0: SHFLBW_WAIT_VMCNT(0); break;
-                case 1: SHFLBW_WAIT_VMCNT(SLAB_IPL); break;
-                case 2: SHFLBW_WAIT_VMCNT(2 * SLAB_IPL); break;
-                default: SHFLBW_WAIT_VMCNT(3 * SLAB_IPL); break;
+                case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+                case 1: asm volatile("s_waitcnt vmcnt(%0)" :: "n"(SLAB_IPL) : "memory"); break;
+                case 2: asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * SLAB_IPL) : "memory"); break;
+                default: asm volatile("s_waitcnt vmcnt(%0)" :: "n"(3 * SLAB_IPL) : "memory"); break;
             }
             static_assert(SLAB_LEAD <= 4, "extend the switch above");
-            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the zero-row write
-            __builtin_amdgcn_s_barrier();
-            // after the barrier nobody reads chunk c-WINDOW any more: its stage
-            // takes chunk c+LEAD
-            if (c + SLAB_LEAD < C) issue_chunk(c + SLAB_LEAD);
+            landed[lw] = c + 1;
+            const int j = c + SLAB_LEAD;
+            if (j < C) {
+                // chunk j takes the stage of chunk j-STAGES, whose last readers run
+                // in iteration j-LEAD-1 = c-1
+                if (j >= SLAB_STAGES)
+                    for (int tries = 0; !reached(progress, GW, c) && tries < SLAB_SPIN_LIMIT; ++tries)
+                        __builtin_amdgcn_s_sleep(1);
+                asm volatile("" ::: "memory");
+                issue_chunk(j);
+            }
         }
-        __builtin_amdgcn_s_barrier();  // pairs with the compute wavefronts' last barrier
         return;
     }
 
     // ---------------------------------------------------------------- compute
     const int g = gb * GW + wave;
     const bool have_group = g < a.A.G;
-    int sbeg = 0, nsteps = 0;
-    const int32_t* my_iter = a.iter_ptr;
-    if (have_group) {
-        sbeg = a.A.step_ptr[g];
-        nsteps = a.A.step_ptr[g + 1] - sbeg;
-        my_iter = a.iter_ptr + (long)g * (C + 1);
+    if (!have_group) {
+        progress[wave] = C;  // nothing to read: never hold a stage back
+        return;
     }
+    const int sbeg = a.A.step_ptr[g];
+    const int nsteps = a.A.step_ptr[g + 1] - sbeg;  // a multiple of PD
 
     const int bl = lane >> 4, il = lane & 15;
     // 16-byte chunk (before the tile offset) and byte inside it that this lane reads
@@ -207,67 +225,54 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     constexpr int ROWS_E = SMALL ? 16 : 32;
     int out_row[RB][ROWS_E / 8];
     {
-        const int32_t* rows_g = a.A.row_indices + (long)(have_group ? g : 0) * V;
+        const int32_t* rows_g = a.A.row_indices + (long)g * V;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int i = 0; i < ROWS_E / 8; ++i) out_row[rb][i] = rows_g[rb * 32 + i * 8 + (lane >> 3)];
     }
 
-    // BulkLoadMeta: each step's weight tile (RB KB, already in operand order)
-    // and lane table (256 B) are brought into this wavefront's LDS ring by
-    // direct loads issued RING-1 steps ahead.  Nothing else sits in this
-    // wavefront's vector-memory queue inside the loop, and every step issues
-    // exactly LPS loads (the step index is clamped at the end), so "the
-    // current step's metadata has landed" is vmcnt(META_WAIT).
-    const int last = nsteps > 0 ? nsteps - 1 : 0;
-    const char* val_g = reinterpret_cast<const char*>(a.A.values) + ((long)sbeg * RB * 64 + lane) * 16;
-    const char* tab_g = reinterpret_cast<const char*>(a.table) + ((long)sbeg * 64 + lane) * 4;
-    char* my_ring = smem + SLAB_X_BYTES + wave * (RING * SLOT_BYTES);
-    const unsigned ring_off = (unsigned)(size_t)(lds_char_ptr)my_ring;
-    auto issue_meta = [&](int step, int slot) __attribute__((always_inline)) {
-        const int sn = step < nsteps ? step : last;
-        const unsigned dst = ring_off + slot * SLOT_BYTES;
+    // BulkLoadMeta: table word and weight operand of the next PD steps sit in PD
+    // register sets; step s uses set s % PD and refills it for step s + PD (the
+    // index is clamped at the end, so the loads are unconditional).
+    const int last = nsteps - 1;
+    const uint32_t* tabp = a.table + (long)sbeg * 64 + lane;
+    const half8* valp = a.A.values + (long)sbeg * RB * 64 + lane;
+    unsigned mt[PD];
+    half8 mw[PD][RB];
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-            meta_dma16(val_g + ((long)sn * RB + rb) * 1024, dst + rb * 1024);
-        meta_dma4(tab_g + (long)sn * 256, dst + RB * 1024);
-    };
+    for (int u = 0; u < PD; ++u) {
+        mt[u] = 0;
 #pragma unroll
-    for (int u = 0; u < RING - 1; ++u) issue_meta(u, u);
-
-    // iter_ptr[c+1] for 64 iterations at a time, one entry per lane
-    int itv = 0;
-    int s = 0;
-    int slot = 0;  // s % RING
-
-    for (int c = 0; c < C; ++c) {
-        if ((c & 63) == 0) {
-            const int idx = c + 1 + lane;
-            itv = have_group ? my_iter[idx < C ? idx : C] : 0;
-            // consume the value here, so that the wait for this load sits inside
-            // this rarely taken block and not in front of every iteration
-            asm volatile("" : "+v"(itv));
+        for (int rb = 0; rb < RB; ++rb) mw[u][rb] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+        if (nsteps > 0) {
+            mt[u] = tabp[(long)u * 64];
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) mw[u][rb] = valp[((long)u * RB + rb) * 64];
         }
-        const int s_end = __builtin_amdgcn_readlane(itv, c & 63);
-        // chunks up to c are in LDS for everybody; c-WINDOW+1 .. c are readable
-        __syncthreads();
-        for (; s < s_end; ++s) {
-            // refill the slot the previous step has just released
-            {
-                int free_slot = slot - 1;
-                free_slot = free_slot < 0 ? RING - 1 : free_slot;
-                issue_meta(s + RING - 1, free_slot);
-            }
-            asm volatile("s_waitcnt vmcnt(%0)" :: "n"(META_WAIT) : "memory");
-            const char* sl = my_ring + slot * SLOT_BYTES;
-            const unsigned tab = *reinterpret_cast<const unsigned*>(sl + RB * 1024 + lane * 4);
-            half8 w[RB];
+    }
+
+    int cur = 0;  // chunk of the step in hand; every step of an earlier chunk is done
+    for (int s0 = 0; s0 < nsteps; s0 += PD) {
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) w[rb] = *reinterpret_cast<const half8*>(sl + rb * 1024 + lane * 16);
-            const int row0 = tab & 0xffff, row1 = tab >> 16;
+        for (int u = 0; u < PD; ++u) {
+            const unsigned tab = mt[u];
+            const int e = __builtin_amdgcn_readfirstlane(tab >> 18);
+            if (e != cur) {
+                // this wavefront's reads of chunks below e - WINDOW + 1 are over
+                asm volatile("" ::: "memory");
+                progress[wave] = e;
+                cur = e;
+            }
+            for (int tries = 0; !reached(landed, SLAB_LOADERS, e + 1) && tries < SLAB_SPIN_LIMIT; ++tries)
+                __builtin_amdgcn_s_sleep(1);
+            asm volatile("" ::: "memory");
+
+            const int row0 = tab & 511, row1 = (tab >> 9) & 511;
             const int base0 = row0 * SLAB_ROW_BYTES + qbyte, swz0 = (row0 & 7) << 1;
             const int base1 = row1 * SLAB_ROW_BYTES + qbyte, swz1 = (row1 & 7) << 1;
+            // all transposed reads of the step go out before the first product
+            half8 x[NT];
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const int q = (SMALL ? 2 * t : 4 * t) + qc;
@@ -276,32 +281,36 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
                 short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (lds_short4_ptr)(smem + base1 + ((q ^ swz1) << 4)));
                 half4 l4 = __builtin_bit_cast(half4, lo), h4 = __builtin_bit_cast(half4, hi);
-                half8 x = {l4[0], l4[1], l4[2], l4[3], h4[0], h4[1], h4[2], h4[3]};
+                x[t] = half8{l4[0], l4[1], l4[2], l4[3], h4[0], h4[1], h4[2], h4[3]};
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
                 if (SMALL) {
-                    acc16[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x, w[0], acc16[t], 0, 0, 0);
+                    acc16[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x[t], mw[u][0], acc16[t], 0, 0, 0);
                 } else {
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb)
-                        acc32[rb][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x, w[rb], acc32[rb][t], 0, 0, 0);
+                        acc32[rb][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[t], mw[u][rb], acc32[rb][t], 0, 0, 0);
                 }
             }
-            slot = (slot + 1 == RING) ? 0 : slot + 1;
+            {
+                const int sn = (s0 + u + PD < nsteps) ? s0 + u + PD : last;
+                mt[u] = tabp[(long)sn * 64];
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) mw[u][rb] = valp[((long)sn * RB + rb) * 64];
+            }
         }
     }
-    // drain the metadata loads still in flight before LDS is reused
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();  // all transposed reads done: the stages become epilogue scratch
+    asm volatile("" ::: "memory");
+    progress[wave] = C;  // all of this wavefront's reads of X are over
 
     // ---- reordered write-back: per wavefront, 32 (16) stored rows x 128 bytes per pass
-    if (!have_group) return;
     constexpr int OUT16 = 16 / (int)sizeof(OutT);        // values per 16 bytes
     constexpr int CW = 128 / (int)sizeof(OutT);           // columns per pass: 64 (fp16) or 32 (fp32)
     constexpr int PASSES = SLAB_TN / CW;
     constexpr int TPP = CW / TILE_N;                      // instruction tiles per pass
     constexpr int EP = CW + OUT16;                        // pitch in OutT units (144 bytes)
-    constexpr int WAVE_BYTES = 32 * 144;
-    static_assert(GW * WAVE_BYTES <= SLAB_STAGES * SLAB_STAGE_BYTES, "epilogue scratch must fit");
-    OutT* ep = reinterpret_cast<OutT*>(smem + wave * WAVE_BYTES);
+    OutT* ep = reinterpret_cast<OutT*>(smem + SCRATCH_OFF + wave * WAVE_BYTES);
     const int erow = lane >> 3, echunk = lane & 7;        // 8 lanes x 16 B per row
     typedef OutT vec4 __attribute__((ext_vector_type(4)));
     typedef OutT vecw __attribute__((ext_vector_type(OUT16)));
