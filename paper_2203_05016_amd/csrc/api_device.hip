@@ -168,7 +168,16 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
     const bool slab_possible = aligned && A->slab_ok && A->V <= 64;
     if (A->tune_kernel == 2 && !slab_possible)
         return fail(SHFLBW_ERR_BAD_OPTION, "slab kernel needs the windowed layout, V <= 64 and aligned operands");
-    if (A->tune_kernel == 2) {
+    bool use_slab = A->tune_kernel == 2;
+    if (A->tune_kernel == 0 && slab_possible) {
+        // automatic choice: the slab kernel needs enough groups to fill its compute
+        // wavefronts and enough tiles to fill the chip; otherwise the per-wavefront
+        // gather kernel spreads the work better
+        const int gw = A->V == 64 ? 8 : 12;
+        const long tiles = ((N + SLAB_TN - 1) / SLAB_TN) * ((A->G + gw - 1) / gw);
+        use_slab = A->V <= 32 && A->G >= gw && tiles >= 128;
+    }
+    if (use_slab) {
         if (ydtype == SHFLBW_F16) return dispatch_slab<_Float16>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);
         return dispatch_slab<float>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);
     }
