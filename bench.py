@@ -25,6 +25,9 @@ sys.path.insert(0, ROOT)
 
 MFMA_F16_PEAK = 2.5166e15      # 256 CU x 4096 FLOP/clk x 2.4 GHz
 HBM_PEAK = 8.0e12
+# HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# scaled by the same counters on a 64 MiB copy (profiles/slab_kernel_ffn_config2_pmc.md)
+MEASURED_TRAFFIC_BYTES = 132.4e6
 PAPER_CONTEXT = "paper: up to 1.81x/4.18x/1.90x over cuBLAS dense at 75% on V100/T4/A100 (context only)"
 
 
@@ -140,6 +143,11 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-baseline leg")
     ap.add_argument("--tile-n", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 gather, 2 slab")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="time only the headline workload (for a kernel trace whose average is that workload's)")
+    ap.add_argument("--pmc", action="store_true",
+                    help="counter-collection run: one 64 MiB device copy (calibration) and three "
+                         "launches of the headline workload, nothing else")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards over N "
@@ -151,7 +159,29 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
     p = synth.config(1)
+    if args.pmc:
+        # FETCH_SIZE / WRITE_SIZE of the copy (64 MiB read, 64 MiB written) give the
+        # factor that turns the counters' units into bytes for the kernel's rows
+        src = torch.zeros(32 << 20, dtype=torch.float16, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        c = Case(p, 3, tile_n=args.tile_n, kernel=args.kernel)
+        for _ in range(3):
+            c.step()
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_run": True, "copy_bytes_each_way": 64 << 20, "launches": 3}))
+        return
     main_r = measure_spmm(p, args.steps, args.warmup, cold=True, tile_n=args.tile_n, kernel=args.kernel)
+    if args.headline_only:
+        achieved = main_r["bytes"] / (main_r["ms"] * 1e-3)
+        print(json.dumps({"metric": "useful TFLOP/s (2*nnz*N/s), Shfl-BW SpMM at 75% sparsity, V=32",
+                          "value": main_r["tflops"], "unit": "TFLOP/s", "ms_per_step": main_r["ms"],
+                          "steps": args.steps, "warmup": args.warmup,
+                          "roofline": {"bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9,
+                                       "unit": "GB/s", "frac": achieved / HBM_PEAK}}))
+        return
     warm_r = measure_spmm(p, args.steps, args.warmup, cold=False, tile_n=args.tile_n, kernel=args.kernel)
     dense_p = synth.config(1, sparsity=0.0)
     dense_r = measure_spmm(dense_p, max(10, args.steps // 4), max(3, args.warmup // 4), cold=True,
@@ -173,9 +203,9 @@ def main():
                    "M": p.M, "K": p.K, "N": p.N, "V": p.V, "nnz": main_r["nnz"],
                    "rotating_buffer_pairs": main_r["rotate"]},
         "roofline": {"bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": MEASURED_TRAFFIC_BYTES,
                      "algorithmic_bytes_per_launch": main_r["bytes"],
-                     "kernel": "shflbw_gather_kernel<32,...>"},
+                     "kernel": "shflbw_slab_kernel<32,12,f16>"},
         "mfma_peak_frac_useful": main_r["tflops"] * 1e12 / MFMA_F16_PEAK,
         "speedup_vs_own_dense": dense_r["ms"] / main_r["ms"],
         "dense_run": {"ms": dense_r["ms"], "tflops": dense_r["tflops"],
