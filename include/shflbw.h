@@ -113,8 +113,9 @@ size_t shflbw_device_bytes(const shflbw_matrix* A);
 int shflbw_bind_device(shflbw_matrix* A, void* dev_buf, void* stream);
 
 /* Kernel selection, for measurement.  kernel: 0 = automatic, 1 = per-wave
- * gather kernel, 2 = shared-slab kernel (shflbw_spmm then fails with
- * SHFLBW_ERR_BAD_OPTION when the matrix or the operands do not allow it).
+ * gather kernel, 2 = shared-slab kernel for shflbw_spmm / staged kernel for
+ * shflbw_conv2d (the call then fails with SHFLBW_ERR_BAD_OPTION when the
+ * matrix, the operands or the shape do not allow it).
  * tile_n: 0 = automatic, else the number of output columns one wavefront of
  * the gather kernel owns (64 or 128). */
 int shflbw_set_tuning(shflbw_matrix* A, int kernel, int tile_n);
@@ -140,6 +141,9 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
  *  in   device, binary16: [batch][C_in][H][W] (NCHW) or [C_in][H][W][batch] (CHWN).
  *  out  device, ydtype:   [batch][C_out][H_out][W_out] or [C_out][H_out][W_out][batch],
  *       H_out = (H + 2*pad_h - R)/stride_h + 1, W_out likewise.
+ * For V = 32 and 64 a workgroup copies the part of the input its output
+ * positions can touch into LDS once and gathers from there; other V, and
+ * inputs with too many channels for that, take the per-wave gather kernel.
  */
 int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out,
                   int batch, int C_in, int H, int W, int R, int S,

@@ -7,6 +7,7 @@
 
 #include "gather_kernel.hip"
 #include "slab_kernel.hip"
+#include "conv_kernel.hip"
 #include "shflbw_internal.h"
 
 namespace shflbw {
@@ -107,6 +108,94 @@ int dispatch_out(const shflbw_matrix* A, const Geom& geom, long N, shflbw_dtype 
 {
     if (ydtype == SHFLBW_F16) return dispatch_v<_Float16, Geom>(A, geom, N, stream);
     return dispatch_v<float, Geom>(A, geom, N, stream);
+}
+
+// Picks the box of output positions one workgroup of the staged convolution
+// kernel owns, and fills the geometry part of its arguments.  Returns false
+// when no box fits (too many channels for the LDS, or a V the kernel does not
+// cover); the caller then takes the gather kernel.
+bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S, int sh, int sw,
+               int ph, int pw, int Ho, int Wo, bool chwn, ConvArgs& a, size_t& lds_bytes)
+{
+    if (A->V != 32 && A->V != 64) return false;
+    const int gblocks = (A->G + CONV_GW - 1) / CONV_GW;
+    const size_t koff_bytes = (((size_t)A->K * 2) + 15) / 16 * 16;
+    const size_t lds_cap = 160 * 1024 - 512;
+    auto staged_elems = [&](int th, int tw, int tb) {
+        return ((size_t)C + 1) * ((size_t)(th - 1) * sh + R) * ((size_t)(tw - 1) * sw + S) * tb;
+    };
+    auto fits = [&](int th, int tw, int tb) {
+        const size_t e = staged_elems(th, tw, tb);
+        return e <= 65535 && e * 2 + 16 + koff_bytes <= lds_cap;   // 16-bit LDS element offsets
+    };
+    int th = 1, tw = 1, tb = 1;
+    long boxes = 0;
+    bool found = false;
+    const int targets[3] = {CONV_TN, 64, 32};
+    for (int target : targets) {
+        int h, w, b;
+        if (chwn) {
+            b = B < target ? B : target;
+            w = Wo < target / b ? Wo : target / b; if (w < 1) w = 1;
+            h = Ho < target / (b * w) ? Ho : target / (b * w); if (h < 1) h = 1;
+        } else {
+            w = Wo < target ? Wo : target;
+            h = Ho < target / w ? Ho : target / w; if (h < 1) h = 1;
+            b = B < target / (w * h) ? B : target / (w * h); if (b < 1) b = 1;
+        }
+        // shrink the box until it fits: the slowest-running dimension of the local index first
+        while (!fits(h, w, b) && (h > 1 || w > 1 || b > 1)) {
+            if (chwn) {
+                if (h > 1) --h;
+                else if (w > 1) w = (w + 1) / 2;
+                else b = (b + 1) / 2;
+            } else {
+                if (b > 1) b = (b + 1) / 2;
+                else if (h > 1) --h;
+                else w = (w + 1) / 2;
+            }
+        }
+        if (!fits(h, w, b)) continue;
+        th = h; tw = w; tb = b; found = true;
+        boxes = (long)((B + b - 1) / b) * ((Ho + h - 1) / h) * ((Wo + w - 1) / w);
+        if (boxes * gblocks >= 256) break;   // enough workgroups to fill the chip
+    }
+    if (!found || boxes * gblocks > 0x7fffffffL) return false;
+    a.B = B; a.C = C; a.H = H; a.W = W; a.R = R; a.S = S; a.sh = sh; a.sw = sw; a.ph = ph; a.pw = pw;
+    a.Ho = Ho; a.Wo = Wo; a.K = A->K;
+    if (chwn) {
+        a.isB = 1; a.isW = B; a.isH = (long)W * B; a.isC = (long)H * W * B;
+        a.osB = 1; a.osW = B; a.osH = (long)Wo * B; a.osM = (long)Ho * Wo * B;
+    } else {
+        a.isW = 1; a.isH = W; a.isC = (long)H * W; a.isB = (long)C * H * W;
+        a.osW = 1; a.osH = Wo; a.osM = (long)Ho * Wo; a.osB = (long)A->M * Ho * Wo;
+    }
+    a.th = th; a.tw = tw; a.tb = tb;
+    a.ny = (Ho + th - 1) / th; a.nx = (Wo + tw - 1) / tw; a.nb = (B + tb - 1) / tb;
+    a.rows_in = (th - 1) * sh + R; a.cols_in = (tw - 1) * sw + S;
+    a.b_fast = chwn ? 1 : 0;
+    a.gblocks = gblocks;
+    size_t in_bytes = (staged_elems(th, tw, tb) * 2 + 15) / 16 * 16;
+    const size_t scratch = (size_t)CONV_GW * CONV_SCRATCH;
+    if (in_bytes < scratch) in_bytes = scratch;
+    a.in_bytes = (int)in_bytes;
+    lds_bytes = in_bytes + koff_bytes;
+    return true;
+}
+
+template <int V, typename OutT>
+int launch_conv(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStream_t stream)
+{
+    a.A = view_of(A);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shflbw_conv_kernel<V, OutT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    const long wgs = (long)a.nb * a.ny * a.nx * a.gblocks;
+    hipLaunchKernelGGL((shflbw_conv_kernel<V, OutT>), dim3((unsigned)wgs), dim3(64 * CONV_GW), lds_bytes,
+                       stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return SHFLBW_OK;
 }
 
 int check_bound(const shflbw_matrix* A)
@@ -220,6 +309,24 @@ int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, 
         return fail(SHFLBW_ERR_BAD_SHAPE, "tensor above 2^31 elements");
     int rc = check_bound(A);
     if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (A->tune_kernel != 1) {
+        ConvArgs ca;
+        size_t lds_bytes = 0;
+        if (plan_conv(A, batch, C_in, H, W, R, S, stride_h, stride_w, pad_h, pad_w, Ho, Wo,
+                      layout == SHFLBW_CHWN, ca, lds_bytes)) {
+            ca.in = static_cast<const _Float16*>(in);
+            ca.out = out;
+            if (A->V == 32)
+                return ydtype == SHFLBW_F16 ? launch_conv<32, _Float16>(A, ca, lds_bytes, st)
+                                            : launch_conv<32, float>(A, ca, lds_bytes, st);
+            return ydtype == SHFLBW_F16 ? launch_conv<64, _Float16>(A, ca, lds_bytes, st)
+                                        : launch_conv<64, float>(A, ca, lds_bytes, st);
+        }
+        if (A->tune_kernel == 2)
+            return fail(SHFLBW_ERR_BAD_OPTION,
+                        "staged convolution kernel needs V = 32 or 64 and an input box that fits the LDS");
+    }
     GeomConv g;
     g.in = static_cast<const _Float16*>(in);
     g.out = out;
@@ -227,7 +334,7 @@ int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, 
     g.sh = stride_h; g.sw = stride_w; g.ph = pad_h; g.pw = pad_w; g.Ho = Ho; g.Wo = Wo;
     g.chwn = (layout == SHFLBW_CHWN);
     g.N = N;
-    return dispatch_out(A, g, (long)N, ydtype, static_cast<hipStream_t>(stream));
+    return dispatch_out(A, g, (long)N, ydtype, st);
 }
 
 }  // extern "C"

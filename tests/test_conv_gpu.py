@@ -10,11 +10,13 @@ from gpu_util import announce
 pytestmark = pytest.mark.gpu
 
 
-def _run_conv(p, out_dtype="float16", tile_n=0):
+def _run_conv(p, out_dtype="float16", tile_n=0, kernel=0):
+    """kernel: 0 automatic (the staged kernel where it applies), 1 gather
+    kernel, 2 staged kernel or an error."""
     import torch
     g = p.conv
     A = binding.compress(p.W, p.mask, p.perm, p.V)
-    A.set_tuning(0, tile_n)
+    A.set_tuning(kernel, tile_n)
     A.bind_device("cuda:0")
     x = torch.from_numpy(g["input"]).to("cuda:0")
     shape = (g["batch"], g["Cout"], g["Ho"], g["Wo"]) if g["layout"] == "NCHW" else \
@@ -41,8 +43,10 @@ def test_conv_small_shapes(layout, stride, pad, R, S):
     announce("conv small", layout, stride, pad, R, S)
     p = synth.make_conv(3, 24, 9, 7, 64, R, S, 32, 0.6, seed=201, stride=stride, pad=pad,
                         layout=layout)
-    _parity(p)
-    _parity(p, out_dtype="float32", tile_n=64)
+    _parity(p, kernel=2)
+    _parity(p, kernel=1)
+    _parity(p, out_dtype="float32", kernel=2)
+    _parity(p, out_dtype="float32", tile_n=64, kernel=1)
 
 
 @pytest.mark.parametrize("V", [16, 64])
@@ -51,6 +55,9 @@ def test_conv_other_group_sizes_integer_exact(V):
     p = synth.make_conv(2, 16, 7, 7, 2 * V, 3, 3, V, 0.75, seed=202, pad=(1, 1), integer=True)
     g = p.conv
     got = _run_conv(p, out_dtype="float32")
+    if V == 64:  # the staged kernel covers V = 32 and 64; both kernels must agree bit for bit
+        assert np.array_equal(got, _run_conv(p, out_dtype="float32", kernel=1))
+        assert np.array_equal(got, _run_conv(p, out_dtype="float32", kernel=2))
     want, _ = c_oracle.conv2d(p.W, p.mask, g["input"], 3, 3, (1, 1), (1, 1))
     assert np.array_equal(got.astype(np.float64), want)
 
@@ -69,8 +76,31 @@ def test_conv_1x1_equals_spmm_path_bitwise():
     assert np.array_equal(got.reshape(64, 200).view(np.uint16), Y.cpu().numpy().view(np.uint16))
 
 
+@pytest.mark.parametrize("layout,batch,Cin,H,Wd,Cout,V", [
+    ("NCHW", 2, 8, 6, 150, 32, 32),     # rows wider than a box: several boxes along x
+    ("CHWN", 40, 8, 6, 50, 32, 32),     # batch innermost, boxes of a few positions x all images
+    ("NCHW", 5, 300, 12, 12, 32, 32),   # many channels: the staged box shrinks to fit the LDS
+    ("NCHW", 3, 16, 10, 10, 640, 64),   # V = 64, ten groups: two blocks of groups per box
+    ("CHWN", 130, 4, 3, 3, 32, 32),     # more images than one box holds
+])
+def test_conv_staged_kernel_box_shapes(layout, batch, Cin, H, Wd, Cout, V):
+    announce("conv boxes", layout, batch, Cin, H, Wd, Cout, V)
+    p = synth.make_conv(batch, Cin, H, Wd, Cout, 3, 3, V, 0.5, seed=204, pad=(1, 1), layout=layout)
+    _parity(p, kernel=2)
+    _parity(p, kernel=1)
+
+
+def test_conv_staged_kernel_refuses_what_it_cannot_hold():
+    """Forcing the staged kernel on V = 16 is an error, not a silent switch."""
+    announce("conv staged refusal")
+    p = synth.make_conv(2, 16, 7, 7, 32, 3, 3, 16, 0.5, seed=205, pad=(1, 1))
+    with pytest.raises(binding.ShflbwError):
+        _run_conv(p, kernel=2)
+
+
 def test_config4_resnet_conv_full():
-    """Config 4 at full size (32x256x14x14, 3x3, pad 1, V=32, 75 %)."""
+    """Config 4 at full size (32x256x14x14, 3x3, pad 1, V=32, 75 %), both kernels."""
     announce("config4")
     p = synth.config(3)
-    _parity(p)
+    _parity(p, kernel=2)
+    _parity(p, kernel=1)
