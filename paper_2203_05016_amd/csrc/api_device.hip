@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstring>
 #include <string>
 
 #include "gather_kernel.hip"
@@ -119,45 +120,53 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
 {
     if (A->V != 32 && A->V != 64) return false;
     const int gblocks = (A->G + CONV_GW - 1) / CONV_GW;
-    const size_t koff_bytes = (((size_t)A->K * 2) + 15) / 16 * 16;
+    const size_t list_bytes = CONV_LIST_BYTES;   // per-wavefront lists of LDS offsets
     const size_t lds_cap = 160 * 1024 - 512;
+    const double kg_avg = A->G > 0 ? (double)A->nnz / ((double)A->V * A->G) : 0.0;
+    const double groups_per_box = A->G < CONV_GW ? A->G : CONV_GW;
     auto staged_elems = [&](int th, int tw, int tb) {
         return ((size_t)C + 1) * ((size_t)(th - 1) * sh + R) * ((size_t)(tw - 1) * sw + S) * tb;
     };
     auto fits = [&](int th, int tw, int tb) {
         const size_t e = staged_elems(th, tw, tb);
-        return e <= 65535 && e * 2 + 16 + koff_bytes <= lds_cap;   // 16-bit LDS element offsets
+        return e <= 65535 && e * 2 + 16 + list_bytes <= lds_cap;   // 16-bit LDS element offsets
     };
+    // Candidate boxes: every split of at most `target` positions into images x rows x
+    // columns whose innermost-running dimension keeps runs of 8 where the tensor allows
+    // it.  The cost of a split is what all its boxes together read: the staged input
+    // (global loads, weighted 4x; the halo of a small box is read again by its
+    // neighbours) plus the LDS gathers of every 32-position instruction tile, ragged
+    // edge tiles included.
     int th = 1, tw = 1, tb = 1;
     long boxes = 0;
     bool found = false;
     const int targets[3] = {CONV_TN, 64, 32};
     for (int target : targets) {
-        int h, w, b;
-        if (chwn) {
-            b = B < target ? B : target;
-            w = Wo < target / b ? Wo : target / b; if (w < 1) w = 1;
-            h = Ho < target / (b * w) ? Ho : target / (b * w); if (h < 1) h = 1;
-        } else {
-            w = Wo < target ? Wo : target;
-            h = Ho < target / w ? Ho : target / w; if (h < 1) h = 1;
-            b = B < target / (w * h) ? B : target / (w * h); if (b < 1) b = 1;
-        }
-        // shrink the box until it fits: the slowest-running dimension of the local index first
-        while (!fits(h, w, b) && (h > 1 || w > 1 || b > 1)) {
-            if (chwn) {
-                if (h > 1) --h;
-                else if (w > 1) w = (w + 1) / 2;
-                else b = (b + 1) / 2;
-            } else {
-                if (b > 1) b = (b + 1) / 2;
-                else if (h > 1) --h;
-                else w = (w + 1) / 2;
+        double best_cost = 0;
+        int bh = 0, bw = 0, bb = 0;
+        for (int b = 1; b <= B && b <= target; b = (b < B && 2 * b > B) ? B : 2 * b) {
+            if (chwn && b < 8 && b < B) continue;
+            for (int w = 1; w <= Wo && b * w <= target; ++w) {
+                if (!chwn && w < 8 && w < Wo) continue;
+                int h = target / (b * w);
+                if (h > Ho) h = Ho;
+                if (h < 1) continue;
+                while (h > 1 && !fits(h, w, b)) --h;
+                if (!fits(h, w, b)) continue;
+                const int npos = b * w * h;
+                const double nboxes = (double)((B + b - 1) / b) * ((Ho + h - 1) / h) * ((Wo + w - 1) / w);
+                const double cost = nboxes * (4.0 * staged_elems(h, w, b) +
+                                              (double)((npos + 31) / 32) * 32.0 * kg_avg * groups_per_box);
+                if (bh == 0 || cost < best_cost * (1 - 1e-9) ||
+                    (cost < best_cost * (1 + 1e-9) && npos > bb * bw * bh)) {
+                    best_cost = cost; bh = h; bw = w; bb = b;
+                }
             }
+            if (b == B) break;
         }
-        if (!fits(h, w, b)) continue;
-        th = h; tw = w; tb = b; found = true;
-        boxes = (long)((B + b - 1) / b) * ((Ho + h - 1) / h) * ((Wo + w - 1) / w);
+        if (bh == 0) continue;
+        th = bh; tw = bw; tb = bb; found = true;
+        boxes = (long)((B + tb - 1) / tb) * ((Ho + th - 1) / th) * ((Wo + tw - 1) / tw);
         if (boxes * gblocks >= 256) break;   // enough workgroups to fill the chip
     }
     if (!found || boxes * gblocks > 0x7fffffffL) return false;
@@ -179,23 +188,32 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     const size_t scratch = (size_t)CONV_GW * CONV_SCRATCH;
     if (in_bytes < scratch) in_bytes = scratch;
     a.in_bytes = (int)in_bytes;
-    lds_bytes = in_bytes + koff_bytes;
+    lds_bytes = in_bytes + list_bytes;
     return true;
+}
+
+template <int V, int NT, typename OutT>
+int launch_conv_nt(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStream_t stream)
+{
+    a.A = view_of(A);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shflbw_conv_kernel<V, NT, OutT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    const long wgs = (long)a.nb * a.ny * a.nx * a.gblocks;
+    hipLaunchKernelGGL((shflbw_conv_kernel<V, NT, OutT>), dim3((unsigned)wgs), dim3(64 * CONV_GW), lds_bytes,
+                       stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return SHFLBW_OK;
 }
 
 template <int V, typename OutT>
 int launch_conv(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStream_t stream)
 {
-    a.A = view_of(A);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shflbw_conv_kernel<V, OutT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
-    const long wgs = (long)a.nb * a.ny * a.nx * a.gblocks;
-    hipLaunchKernelGGL((shflbw_conv_kernel<V, OutT>), dim3((unsigned)wgs), dim3(64 * CONV_GW), lds_bytes,
-                       stream, a);
-    e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(e, "kernel launch");
-    return SHFLBW_OK;
+    const int npos = a.tb * a.th * a.tw;
+    if (npos <= 32) return launch_conv_nt<V, 1, OutT>(A, a, lds_bytes, stream);
+    if (npos <= 64) return launch_conv_nt<V, 2, OutT>(A, a, lds_bytes, stream);
+    return launch_conv_nt<V, 4, OutT>(A, a, lds_bytes, stream);
 }
 
 int check_bound(const shflbw_matrix* A)
@@ -311,10 +329,22 @@ int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, 
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (A->tune_kernel != 1) {
-        ConvArgs ca;
-        size_t lds_bytes = 0;
-        if (plan_conv(A, batch, C_in, H, W, R, S, stride_h, stride_w, pad_h, pad_w, Ho, Wo,
-                      layout == SHFLBW_CHWN, ca, lds_bytes)) {
+        // the plan depends on the matrix and the geometry only: keep the last one
+        struct PlanKey { const shflbw_matrix* A; int64_t nnz; int v[14]; };
+        static thread_local PlanKey last_key = {nullptr, 0, {0}};
+        static thread_local bool last_ok = false;
+        static thread_local ConvArgs last_args;
+        static thread_local size_t last_lds = 0;
+        const PlanKey key = {A, A->nnz, {A->K, A->V, A->G, batch, C_in, H, W, R * 65536 + S,
+                                         stride_h * 65536 + stride_w, pad_h, pad_w, (int)layout, A->M, 0}};
+        if (memcmp(&key, &last_key, sizeof key) != 0) {
+            last_ok = plan_conv(A, batch, C_in, H, W, R, S, stride_h, stride_w, pad_h, pad_w, Ho, Wo,
+                                layout == SHFLBW_CHWN, last_args, last_lds);
+            last_key = key;
+        }
+        if (last_ok) {
+            ConvArgs ca = last_args;
+            const size_t lds_bytes = last_lds;
             ca.in = static_cast<const _Float16*>(in);
             ca.out = out;
             if (A->V == 32)

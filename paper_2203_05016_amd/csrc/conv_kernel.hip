@@ -10,12 +10,14 @@
 //     koff[k] + noff[n]
 // where koff depends only on the reduction index (channel plane, kernel row
 // and column) and noff only on the output position (its top-left input
-// element inside the box).  koff for all K reduction indices is tabulated in
-// LDS by the workgroup, noff lives in registers.  A padded slot of a k-step
-// (column index -1) points at an extra all-zero channel plane.
+// element inside the box).  Each wavefront turns the column indices of its
+// group into koff values 64 k-steps at a time and keeps them in a private LDS
+// list (one 16-byte read per lane and step in the loop); noff lives in
+// registers.  A padded slot of a k-step (column index -1) points at an extra
+// all-zero channel plane.
 //
-// Algorithm 1's parts: BulkLoadMeta = the 16 column indices and the weight
-// operand of the next k-step are fetched while the current one is multiplied;
+// Algorithm 1's parts: BulkLoadMeta = column indices in bulks of 64 k-steps,
+// the weight operand eight (V = 64: four) k-steps ahead in as many register sets;
 // StitchTile = the LDS gather above (each lane reads the 8 reduction indices
 // x up to 4 positions it feeds to the matrix cores); WarpMMA =
 // v_mfma_f32_32x32x16_f16 with the activation tile as first operand;
@@ -39,6 +41,8 @@ namespace shflbw {
 constexpr int CONV_GW = 8;             // compute wavefronts (row groups) per workgroup
 constexpr int CONV_TN = 128;           // most output positions per workgroup
 constexpr int CONV_SCRATCH = 32 * 33 * 4;  // write-back scratch of one wavefront (fp32, pitch 33)
+constexpr int CONV_BULK = 64;          // k-steps of koff values a wavefront holds at a time
+constexpr int CONV_LIST_BYTES = CONV_GW * CONV_BULK * 16 * 2;
 
 struct ConvArgs {
     PackedView A;
@@ -55,18 +59,20 @@ struct ConvArgs {
     int in_bytes;             // LDS bytes reserved for the staged input (and the scratch)
 };
 
-template <int V, typename OutT>
+// NT: 32-position instruction tiles per box (1, 2 or 4; a box holds at most 32*NT positions).
+template <int V, int NT, typename OutT>
 __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
 {
     constexpr int RB = V / 32;
-    constexpr int NT = CONV_TN / 32;
+    constexpr int CONV_PD = RB == 1 ? 8 : 4;   // k-steps the weight operand is fetched ahead
+    static_assert(CONV_BULK % CONV_PD == 0, "bulk boundaries fall on batch boundaries");
     extern __shared__ __attribute__((aligned(16))) char conv_smem[];
     _Float16* xin = reinterpret_cast<_Float16*>(conv_smem);
-    uint16_t* koff = reinterpret_cast<uint16_t*>(conv_smem + a.in_bytes);
-
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // this wavefront's list of koff values: CONV_BULK steps x 16 slots
+    uint16_t* klist = reinterpret_cast<uint16_t*>(conv_smem + a.in_bytes) + wave * (CONV_BULK * 16);
 
     // which box, which block of groups
     int box = blockIdx.x / a.gblocks;
@@ -76,6 +82,40 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     const int b0 = box * a.tb, y0 = by * a.th, x0 = bx * a.tw;
     const int plane = a.rows_in * a.cols_in * a.tb;   // staged elements per channel
     const int iy0 = y0 * a.sh - a.ph, ix0 = x0 * a.sw - a.pw;
+    const int zero_off = a.C * plane;
+    const int RS = a.R * a.S;
+
+    const int g = gb * CONV_GW + wave;
+    const bool have_group = g < a.A.G;
+    const int sbeg = have_group ? a.A.step_ptr[g] : 0;
+    const int nsteps = have_group ? a.A.step_ptr[g + 1] - sbeg : 0;
+
+    // koff values of steps [s0, s0 + CONV_BULK) of this group into the list
+    constexpr int BULK_LOADS = CONV_BULK * 16 / 64;
+    auto load_cols = [&](int s0, int (&cols)[BULK_LOADS]) __attribute__((always_inline)) {
+        const int32_t* cp = a.A.col_idx + ((long)sbeg + s0) * 16;
+        const int avail = (nsteps - s0) * 16;
+#pragma unroll
+        for (int i = 0; i < BULK_LOADS; ++i) {
+            const int j = i * 64 + lane;
+            cols[i] = j < avail ? cp[j] : -1;
+        }
+    };
+    auto store_koff = [&](const int (&cols)[BULK_LOADS]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < BULK_LOADS; ++i) {
+            const int k = cols[i];
+            int off = zero_off;
+            if (k >= 0) {
+                const int c = k / RS, rs = k - c * RS;
+                const int r = rs / a.S, sx = rs - r * a.S;
+                off = c * plane + (r * a.cols_in + sx) * a.tb;
+            }
+            klist[i * 64 + lane] = (uint16_t)off;
+        }
+    };
+    int cols0[BULK_LOADS];
+    load_cols(0, cols0);   // in flight while the input box is staged
 
     // ---- stage the input box: element (c, iy, ix, bb) at xin[c*plane + (iy*cols_in + ix)*tb + bb]
     for (int p = lane; p < plane; p += 64) {
@@ -85,23 +125,24 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
         const int yy = iy0 + iy, xx = ix0 + ix, b = b0 + bb;
         const bool inside = yy >= 0 && yy < a.H && xx >= 0 && xx < a.W && b < a.B;
         const _Float16* src = a.in + (inside ? b * a.isB + yy * a.isH + xx * a.isW : 0);
-#pragma unroll 4
-        for (int c = wave; c < a.C; c += CONV_GW) {
-            _Float16 v = (_Float16)0.f;
-            if (inside) v = src[c * a.isC];
-            xin[c * plane + p] = v;
+        constexpr int MLP = 16;   // loads in flight per lane
+        for (int c0 = wave; c0 < a.C; c0 += CONV_GW * MLP) {
+            _Float16 v[MLP];
+#pragma unroll
+            for (int j = 0; j < MLP; ++j) {
+                const int c = c0 + j * CONV_GW;
+                v[j] = (_Float16)0.f;
+                if (inside && c < a.C) v[j] = src[c * a.isC];
+            }
+#pragma unroll
+            for (int j = 0; j < MLP; ++j) {
+                const int c = c0 + j * CONV_GW;
+                if (c < a.C) xin[c * plane + p] = v[j];
+            }
         }
-        if (wave == 0) xin[a.C * plane + p] = (_Float16)0.f;   // the all-zero plane
+        if (wave == 0) xin[zero_off + p] = (_Float16)0.f;   // the all-zero plane
     }
-    // ---- tabulate koff[k] for k = (c*R + r)*S + s
-    {
-        const int RS = a.R * a.S;
-        for (int k = tid; k < a.K; k += 64 * CONV_GW) {
-            const int c = k / RS, rs = k - c * RS;
-            const int r = rs / a.S, s = rs - r * a.S;
-            koff[k] = (uint16_t)(c * plane + (r * a.cols_in + s) * a.tb);
-        }
-    }
+    store_koff(cols0);
     __syncthreads();
 
     // ---- this lane's output positions: n' = 32*t + lane%32
@@ -119,10 +160,7 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
         noff[t] = live[t] ? (yy * a.sh * a.cols_in + xx * a.sw) * a.tb + bb : 0;
         ooff[t] = live[t] ? (int)(b * a.osB + y * a.osH + x * a.osW) : 0;
     }
-    const int nt_live = (npos + 31) / 32;   // uniform: instruction tiles that hold any position
 
-    const int g = gb * CONV_GW + wave;
-    const bool have_group = g < a.A.G;
     floatx16 acc[RB][NT];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
@@ -131,51 +169,60 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[rb][t][r] = 0.f;
 
-    if (have_group) {
-        const int sbeg = a.A.step_ptr[g];
-        const int nsteps = a.A.step_ptr[g + 1] - sbeg;
+    if (nsteps > 0) {
         const int khalf = lane >> 5;
-        const intx4* colp = reinterpret_cast<const intx4*>(a.A.col_idx + (long)sbeg * 16 + 8 * khalf);
         const half8* valp = a.A.values + (long)sbeg * RB * 64 + lane;
-        const int zero_off = a.C * plane;
+        const int last = nsteps - 1;
+        typedef unsigned short ushort8 __attribute__((ext_vector_type(8)));
+        const ushort8* kl = reinterpret_cast<const ushort8*>(klist) + khalf;   // 8 slots of this lane's half
 
-        intx4 c_lo = {-1, -1, -1, -1}, c_hi = {-1, -1, -1, -1};
-        half8 w[RB];
+        half8 w[CONV_PD][RB];
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) w[rb] = half8{0, 0, 0, 0, 0, 0, 0, 0};
-        if (nsteps > 0) {
-            c_lo = colp[0]; c_hi = colp[1];
+        for (int u = 0; u < CONV_PD; ++u) {
+            const int sn = u < nsteps ? u : last;
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) w[rb] = valp[rb * 64];
+            for (int rb = 0; rb < RB; ++rb) w[u][rb] = valp[((long)sn * RB + rb) * 64];
         }
-        for (int s = 0; s < nsteps; ++s) {
-            // BulkLoadMeta for the next step (clamped, so the loads are unconditional)
-            const int sn = s + 1 < nsteps ? s + 1 : s;
-            const intx4 n_lo = colp[(long)sn * 4], n_hi = colp[(long)sn * 4 + 1];
-            half8 wn[RB];
+        // StitchTile of one step: 8 reduction indices x up to NT positions per lane
+        auto gather = [&](int s, half8 (&x)[NT]) __attribute__((always_inline)) {
+            const ushort8 ko = kl[(s & (CONV_BULK - 1)) * 2];
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) wn[rb] = valp[((long)sn * RB + rb) * 64];
-
-            int ko[8];
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                ko[e] = c_lo[e] < 0 ? zero_off : (int)koff[c_lo[e]];
-                ko[4 + e] = c_hi[e] < 0 ? zero_off : (int)koff[c_hi[e]];
-            }
+                for (int e = 0; e < 8; ++e) x[t][e] = xin[(int)ko[e] + noff[t]];
+        };
+        half8 x_cur[NT], x_nxt[NT];
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                if (t < nt_live) {
-                    half8 x;
+        for (int t = 0; t < NT; ++t) x_cur[t] = x_nxt[t] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+        gather(0, x_cur);
+        for (int s0 = 0; s0 < nsteps; s0 += CONV_PD) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) x[e] = xin[ko[e] + noff[t]];
+            for (int u = 0; u < CONV_PD; ++u) {
+                const int s = s0 + u;
+                if (s < nsteps) {   // uniform
+                    if (s + 1 < nsteps) {
+                        if (((s + 1) & (CONV_BULK - 1)) == 0) {
+                            // next bulk of column indices; step s is already in registers
+                            int cols[BULK_LOADS];
+                            load_cols(s + 1, cols);
+                            SHFLBW_WAVE_LDS_SYNC();   // reads of the old list are over
+                            store_koff(cols);
+                            SHFLBW_WAVE_LDS_SYNC();
+                        }
+                        gather(s + 1, x_nxt);   // in flight while step s is multiplied
+                    }
 #pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-                        acc[rb][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x, w[rb], acc[rb][t], 0, 0, 0);
+                    for (int t = 0; t < NT; ++t)
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb)
+                            acc[rb][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x_cur[t], w[u][rb], acc[rb][t], 0, 0, 0);
+                    const int sn = s + CONV_PD < nsteps ? s + CONV_PD : last;
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb) w[u][rb] = valp[((long)sn * RB + rb) * 64];
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) x_cur[t] = x_nxt[t];
                 }
             }
-            c_lo = n_lo; c_hi = n_hi;
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) w[rb] = wn[rb];
         }
     }
     __syncthreads();   // every wavefront is done reading the staged input; its LDS becomes scratch
@@ -190,7 +237,7 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
         const long my_row = (long)rows_g[rb * 32 + (lane & 31)] * a.osM;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            if (t < nt_live) {
+            {
                 // accumulator register r of lane l: position 8*(r/4) + 4*(l/32) + r%4, stored row l%32
 #pragma unroll
                 for (int r = 0; r < 16; ++r)

@@ -82,6 +82,9 @@ def test_conv_1x1_equals_spmm_path_bitwise():
     ("NCHW", 5, 300, 12, 12, 32, 32),   # many channels: the staged box shrinks to fit the LDS
     ("NCHW", 3, 16, 10, 10, 640, 64),   # V = 64, ten groups: two blocks of groups per box
     ("CHWN", 130, 4, 3, 3, 32, 32),     # more images than one box holds
+    ("NCHW", 4, 8, 96, 96, 32, 32),     # enough positions for boxes of 128 (four instruction tiles)
+    ("NCHW", 4, 8, 72, 72, 32, 32),     # boxes of 64 (two instruction tiles)
+    ("CHWN", 16, 8, 48, 48, 64, 64),    # batch innermost, boxes of 128, V = 64
 ])
 def test_conv_staged_kernel_box_shapes(layout, batch, Cin, H, Wd, Cout, V):
     announce("conv boxes", layout, batch, Cin, H, Wd, Cout, V)
