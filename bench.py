@@ -104,18 +104,43 @@ def measure_spmm(p, steps, warmup, cold=True, **kw):
     return r
 
 
-def measure_conv(p, steps, warmup):
+def measure_conv(p, steps, warmup, pairs=8):
+    """conv2d on rotating input/output pairs (cold operands)."""
     import torch
     from paper_2203_05016_amd import binding
     g = p.conv
     A = binding.compress(p.W, p.mask, p.perm, p.V).bind_device("cuda:0")
-    x = torch.from_numpy(g["input"]).to("cuda:0")
-    out = torch.empty((g["batch"], g["Cout"], g["Ho"], g["Wo"]) if g["layout"] == "NCHW" else
-                      (g["Cout"], g["Ho"], g["Wo"], g["batch"]), dtype=torch.float16, device="cuda:0")
-    fn = lambda: A.conv2d(x, g["R"], g["S"], g["stride"], g["pad"], g["layout"], out=out)
+    shape = (g["batch"], g["Cout"], g["Ho"], g["Wo"]) if g["layout"] == "NCHW" else \
+        (g["Cout"], g["Ho"], g["Wo"], g["batch"])
+    xs = [torch.from_numpy(g["input"]).to("cuda:0") for _ in range(pairs)]
+    outs = [torch.empty(shape, dtype=torch.float16, device="cuda:0") for _ in range(pairs)]
+    state = {"i": 0}
+
+    def fn():
+        j = state["i"] % pairs
+        A.conv2d(xs[j], g["R"], g["S"], g["stride"], g["pad"], g["layout"], out=outs[j])
+        state["i"] += 1
     ms = time_steps(fn, steps, warmup)
     flop = 2.0 * A.info()["nnz"] * p.N
     return dict(ms=ms, tflops=flop / (ms * 1e-3) / 1e12, flop=flop)
+
+
+def measure_library_gemm(p, steps, warmup):
+    """The vendor library's dense fp16 GEMM (torch.matmul) on the same shape,
+    unpruned W, rotating operands: context for the speedup, not part of the path."""
+    import torch
+    rot = rotation_for(p)
+    Wd = torch.from_numpy(p.W).to("cuda:0")
+    Xs = [torch.from_numpy(p.X).to("cuda:0") for _ in range(rot)]
+    Ys = [torch.empty((p.M, p.N), dtype=torch.float16, device="cuda:0") for _ in range(rot)]
+    state = {"i": 0}
+
+    def fn():
+        j = state["i"] % rot
+        torch.matmul(Wd, Xs[j], out=Ys[j])
+        state["i"] += 1
+    ms = time_steps(fn, steps, warmup)
+    return dict(ms=ms, dense_tflops=2.0 * p.M * p.K * p.N / (ms * 1e-3) / 1e12)
 
 
 def cpu_baseline(p):
@@ -189,6 +214,11 @@ def main():
     ident_p = synth.config(1, identity_perm=True)
     ident_r = measure_spmm(ident_p, args.steps, args.warmup, cold=True, tile_n=args.tile_n, kernel=args.kernel)
     conv_r = measure_conv(synth.config(3), args.steps, args.warmup)
+    conv_dense = measure_conv(synth.config(3, sparsity=0.0), max(10, args.steps // 4), max(3, args.warmup // 4))
+    conv_r["speedup_vs_own_dense"] = conv_dense["ms"] / conv_r["ms"]
+    conv_r["dense_ms"] = conv_dense["ms"]
+    lib_r = measure_library_gemm(p, args.steps, args.warmup)
+    lib_r["sparse_speedup_over_library_dense"] = lib_r["ms"] / main_r["ms"]
 
     cpu = None if args.no_cpu else cpu_baseline(p)
 
@@ -213,6 +243,7 @@ def main():
         "warm_cache": {"ms": warm_r["ms"], "tflops": warm_r["tflops"]},
         "identity_perm": {"ms": ident_r["ms"], "shuffled_over_identity": main_r["ms"] / ident_r["ms"]},
         "conv2d_config4": conv_r,
+        "library_dense_gemm": lib_r,
         "cpu_baseline": cpu,
         "context": PAPER_CONTEXT,
     }
