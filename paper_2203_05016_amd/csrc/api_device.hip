@@ -277,12 +277,15 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
         return fail(SHFLBW_ERR_BAD_OPTION, "slab kernel needs the windowed layout, V <= 64 and aligned operands");
     bool use_slab = A->tune_kernel == 2;
     if (A->tune_kernel == 0 && slab_possible) {
-        // automatic choice: the slab kernel needs enough groups to fill its compute
-        // wavefronts and enough tiles to fill the chip; otherwise the per-wavefront
-        // gather kernel spreads the work better
+        // automatic choice, from timings of both kernels over the benchmark shapes: the
+        // slab kernel streams all of X whatever the sparsity, so it pays when enough of
+        // each chunk is used (density), sooner on problems with many tiles; it also
+        // needs enough groups to fill its compute wavefronts
         const int gw = A->V == 64 ? 8 : 12;
         const long tiles = ((N + SLAB_TN - 1) / SLAB_TN) * ((A->G + gw - 1) / gw);
-        use_slab = A->V <= 32 && A->G >= gw && tiles >= 128;
+        const double density = (double)A->nnz / ((double)A->M * A->K);
+        const double need = tiles >= 128 ? 0.11 : (A->V >= 64 ? 0.2 : 0.4);
+        use_slab = A->G >= gw && density >= need;
     }
     if (use_slab) {
         if (ydtype == SHFLBW_F16) return dispatch_slab<_Float16>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     constexpr int RB = SMALL ? 1 : V / 32;
     constexpr int TILE_N = SMALL ? 16 : 32;
     constexpr int NT = SLAB_TN / TILE_N;
-    constexpr int PD = SLAB_UNROLL;                   // register sets of prefetched metadata
+    constexpr int PD = RB >= 2 ? 2 : SLAB_UNROLL;     // register sets of prefetched metadata (divides SLAB_UNROLL)
     constexpr int WAVE_BYTES = 32 * 144;              // write-back scratch of one compute wavefront
     constexpr int SCRATCH_OFF = SLAB_X_BYTES;
     constexpr int FLAGS_OFF = SCRATCH_OFF + GW * WAVE_BYTES;  // landed[4], progress[GW]
@@ -224,13 +224,15 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     // do not queue behind its stores
     constexpr int ROWS_E = SMALL ? 16 : 32;
     int out_row[RB][ROWS_E / 8];
-    {
+    constexpr bool EARLY_ROWS = RB < 2;   // with two row blocks the registers are needed in the loop
+    auto load_rows = [&]() __attribute__((always_inline)) {
         const int32_t* rows_g = a.A.row_indices + (long)g * V;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int i = 0; i < ROWS_E / 8; ++i) out_row[rb][i] = rows_g[rb * 32 + i * 8 + (lane >> 3)];
-    }
+    };
+    if (EARLY_ROWS) load_rows();
 
     // BulkLoadMeta: table word and weight operand of the next PD steps sit in PD
     // register sets; step s uses set s % PD and refills it for step s + PD (the
@@ -303,6 +305,7 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     }
     asm volatile("" ::: "memory");
     progress[wave] = C;  // all of this wavefront's reads of X are over
+    if (!EARLY_ROWS) load_rows();
 
     // ---- reordered write-back: per wavefront, 32 (16) stored rows x 128 bytes per pass
     constexpr int OUT16 = 16 / (int)sizeof(OutT);        // values per 16 bytes
