@@ -37,11 +37,13 @@ def _load():
         i64, vp = ctypes.c_int64, ctypes.c_void_p
         lib.oracle_half_to_double.restype = ctypes.c_double
         lib.oracle_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.oracle_bfloat16_to_double.restype = ctypes.c_double
+        lib.oracle_bfloat16_to_double.argtypes = [ctypes.c_uint16]
         lib.oracle_num_threads.restype = ctypes.c_int
-        lib.oracle_spmm.restype = ctypes.c_int
-        lib.oracle_spmm.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
-        lib.oracle_conv2d.restype = ctypes.c_int
-        lib.oracle_conv2d.argtypes = [vp, vp, vp] + [i64] * 11 + [ctypes.c_int, vp, vp]
+        lib.oracle_spmm_fmt.restype = ctypes.c_int
+        lib.oracle_spmm_fmt.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, ctypes.c_int]
+        lib.oracle_conv2d_fmt.restype = ctypes.c_int
+        lib.oracle_conv2d_fmt.argtypes = [vp, vp, vp] + [i64] * 11 + [ctypes.c_int, vp, vp, ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -50,11 +52,15 @@ def _ptr(a):
     return ctypes.c_void_p(a.ctypes.data)
 
 
-def _f16_bits(a):
+def _bits(a):
+    """(bit patterns, format): float16 arrays are binary16 (format 0); uint16
+    arrays hold bfloat16 bit patterns (format 1; numpy has no such dtype)."""
     a = np.ascontiguousarray(a)
-    if a.dtype != np.float16:
-        raise TypeError("expected float16, got %s" % a.dtype)
-    return a.view(np.uint16)
+    if a.dtype == np.float16:
+        return a.view(np.uint16), 0
+    if a.dtype == np.uint16:
+        return a, 1
+    raise TypeError("expected float16, or uint16 holding bfloat16 bits, got %s" % a.dtype)
 
 
 def num_threads():
@@ -65,9 +71,16 @@ def half_to_double(bits):
     return float(_load().oracle_half_to_double(int(bits)))
 
 
+def bfloat16_to_double(bits):
+    return float(_load().oracle_bfloat16_to_double(int(bits)))
+
+
 def spmm(W, mask, X, want_scale=True):
-    """Y (float64, M x N) and S = |W.mask| |X| for float16 W (M x K), X (K x N)."""
-    Wb, Xb = _f16_bits(W), _f16_bits(X)
+    """Y (float64, M x N) and S = |W.mask| |X| for W (M x K), X (K x N), both
+    float16 or both uint16 arrays of bfloat16 bit patterns."""
+    (Wb, fmt), (Xb, fx) = _bits(W), _bits(X)
+    if fmt != fx:
+        raise TypeError("W and X must have the same format")
     m = np.ascontiguousarray(mask, dtype=np.uint8)
     M, K = Wb.shape
     K2, N = Xb.shape
@@ -75,8 +88,8 @@ def spmm(W, mask, X, want_scale=True):
         raise ValueError("shape mismatch")
     Y = np.empty((M, N), dtype=np.float64)
     S = np.empty((M, N), dtype=np.float64) if want_scale else None
-    rc = _load().oracle_spmm(_ptr(Wb), _ptr(m), _ptr(Xb), M, K, N, _ptr(Y),
-                             _ptr(S) if want_scale else None)
+    rc = _load().oracle_spmm_fmt(_ptr(Wb), _ptr(m), _ptr(Xb), M, K, N, _ptr(Y),
+                                 _ptr(S) if want_scale else None, fmt)
     if rc != 0:
         raise MemoryError("oracle_spmm rc=%d" % rc)
     return (Y, S) if want_scale else Y
@@ -86,7 +99,9 @@ def conv2d(Wt, mask, inp, R, S, stride=(1, 1), pad=(0, 0), layout="NCHW", want_s
     """Masked conv2d.  Wt, mask: (Cout, Cin*R*S), k = (c*R + r)*S + s.
     inp: (B, Cin, H, W) for NCHW or (Cin, H, W, B) for CHWN; the result uses
     the same layout."""
-    Wb, Ib = _f16_bits(Wt), _f16_bits(inp)
+    (Wb, fmt), (Ib, fi) = _bits(Wt), _bits(inp)
+    if fmt != fi:
+        raise TypeError("weights and input must have the same format")
     m = np.ascontiguousarray(mask, dtype=np.uint8)
     lay = {"NCHW": 0, "CHWN": 1}[layout]
     if lay == 0:
@@ -103,9 +118,9 @@ def conv2d(Wt, mask, inp, R, S, stride=(1, 1), pad=(0, 0), layout="NCHW", want_s
     shape = (B, Cout, Ho, Wo) if lay == 0 else (Cout, Ho, Wo, B)
     out = np.empty(shape, dtype=np.float64)
     sc = np.empty(shape, dtype=np.float64) if want_scale else None
-    rc = _load().oracle_conv2d(_ptr(Wb), _ptr(m), _ptr(Ib), B, Cin, H, Wd, Cout, R, S,
-                               sh, sw, ph, pw, lay, _ptr(out),
-                               _ptr(sc) if want_scale else None)
+    rc = _load().oracle_conv2d_fmt(_ptr(Wb), _ptr(m), _ptr(Ib), B, Cin, H, Wd, Cout, R, S,
+                                   sh, sw, ph, pw, lay, _ptr(out),
+                                   _ptr(sc) if want_scale else None, fmt)
     if rc != 0:
         raise RuntimeError("oracle_conv2d rc=%d" % rc)
     return (out, sc) if want_scale else out

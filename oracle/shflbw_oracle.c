@@ -21,9 +21,10 @@
  *
  * with out-of-range input positions contributing zero.
  *
- * Precision: inputs are IEEE binary16 bit patterns, widened exactly to
- * double; every product of two binary16 values is exact in double; sums are
- * accumulated in double.  Alongside Y the oracle returns the scale
+ * Precision: inputs are 16-bit patterns, IEEE binary16 (the half precision
+ * the paper measures in) or bfloat16 (format 1, the other 16-bit operand type
+ * of the matrix cores), widened exactly to double; every product of two such
+ * values is exact in double; sums are accumulated in double.  Alongside Y the oracle returns the scale
  * S[i][j] = sum |W||X| over the same terms, which the parity tolerance
  * (|Y_gpu - Y| <= 2^-10 * S) is stated against.
  *
@@ -56,6 +57,29 @@ double oracle_half_to_double(uint16_t h)
     return sign ? -v : v;
 }
 
+/* bfloat16 -> double from the format's definition: 1 sign bit, 8 exponent
+ * bits (bias 127), 7 fraction bits; exponent 0 is subnormal, 255 is Inf/NaN. */
+double oracle_bfloat16_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 7) & 255;
+    int f = h & 127;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -133);              /* f * 2^-7 * 2^-126 */
+    else if (e == 255)
+        v = f ? NAN : INFINITY;
+    else
+        v = ldexp((double)(128 + f), e - 134);   /* (1 + f/128) * 2^(e-127) */
+    return sign ? -v : v;
+}
+
+/* format 0 = binary16, 1 = bfloat16 */
+static inline double widen(uint16_t h, int format)
+{
+    return format == 1 ? oracle_bfloat16_to_double(h) : oracle_half_to_double(h);
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP
@@ -71,12 +95,12 @@ int oracle_num_threads(void)
  * Y, S: M x N doubles, row-major (S may be NULL).  Returns 0, or -1 when a
  * work buffer cannot be allocated.
  */
-int oracle_spmm(const uint16_t *W, const uint8_t *mask, const uint16_t *X,
-                int64_t M, int64_t K, int64_t N, double *Y, double *S)
+int oracle_spmm_fmt(const uint16_t *W, const uint8_t *mask, const uint16_t *X,
+                    int64_t M, int64_t K, int64_t N, double *Y, double *S, int format)
 {
     double *Xd = (double *)malloc(sizeof(double) * (size_t)(K * N > 0 ? K * N : 1));
     if (!Xd) return -1;
-    for (int64_t t = 0; t < K * N; ++t) Xd[t] = oracle_half_to_double(X[t]);
+    for (int64_t t = 0; t < K * N; ++t) Xd[t] = widen(X[t], format);
 
 #pragma omp parallel for schedule(dynamic, 4)
     for (int64_t i = 0; i < M; ++i) {
@@ -86,7 +110,7 @@ int oracle_spmm(const uint16_t *W, const uint8_t *mask, const uint16_t *X,
         if (s) for (int64_t j = 0; j < N; ++j) s[j] = 0.0;
         for (int64_t k = 0; k < K; ++k) {
             if (!mask[i * K + k]) continue;
-            double w = oracle_half_to_double(W[i * K + k]);
+            double w = widen(W[i * K + k], format);
             const double *x = Xd + k * N;
             for (int64_t j = 0; j < N; ++j) y[j] += w * x[j];
             if (s) {
@@ -97,6 +121,12 @@ int oracle_spmm(const uint16_t *W, const uint8_t *mask, const uint16_t *X,
     }
     free(Xd);
     return 0;
+}
+
+int oracle_spmm(const uint16_t *W, const uint8_t *mask, const uint16_t *X,
+                int64_t M, int64_t K, int64_t N, double *Y, double *S)
+{
+    return oracle_spmm_fmt(W, mask, X, M, K, N, Y, S, 0);
 }
 
 /* Element (b, c, y, x) of an activation tensor in one of two layouts:
@@ -116,10 +146,10 @@ static inline int64_t act_index(int layout, int64_t B, int64_t C, int64_t H, int
  * in the same layout (scale may be NULL).  Ho = (H + 2*ph - R)/sh + 1, same
  * for Wo.  Returns 0, -1 on allocation failure, -2 on an empty output shape.
  */
-int oracle_conv2d(const uint16_t *Wt, const uint8_t *mask, const uint16_t *in,
-                  int64_t B, int64_t Cin, int64_t H, int64_t Wd, int64_t Cout,
-                  int64_t R, int64_t Sk, int64_t sh, int64_t sw, int64_t ph, int64_t pw,
-                  int layout, double *out, double *scale)
+int oracle_conv2d_fmt(const uint16_t *Wt, const uint8_t *mask, const uint16_t *in,
+                      int64_t B, int64_t Cin, int64_t H, int64_t Wd, int64_t Cout,
+                      int64_t R, int64_t Sk, int64_t sh, int64_t sw, int64_t ph, int64_t pw,
+                      int layout, double *out, double *scale, int format)
 {
     if (H + 2 * ph < R || Wd + 2 * pw < Sk) return -2;
     int64_t Ho = (H + 2 * ph - R) / sh + 1;
@@ -128,7 +158,7 @@ int oracle_conv2d(const uint16_t *Wt, const uint8_t *mask, const uint16_t *in,
     int64_t nin = B * Cin * H * Wd;
     double *ind = (double *)malloc(sizeof(double) * (size_t)(nin > 0 ? nin : 1));
     if (!ind) return -1;
-    for (int64_t t = 0; t < nin; ++t) ind[t] = oracle_half_to_double(in[t]);
+    for (int64_t t = 0; t < nin; ++t) ind[t] = widen(in[t], format);
 
 #pragma omp parallel for collapse(2) schedule(dynamic, 4)
     for (int64_t b = 0; b < B; ++b) {
@@ -144,7 +174,7 @@ int oracle_conv2d(const uint16_t *Wt, const uint8_t *mask, const uint16_t *in,
                     for (int64_t s = 0; s < Sk; ++s) {
                         int64_t k = (c * R + r) * Sk + s;
                         if (!mask[o * K + k]) continue;
-                        double w = oracle_half_to_double(Wt[o * K + k]);
+                        double w = widen(Wt[o * K + k], format);
                         for (int64_t y = 0; y < Ho; ++y) {
                             int64_t iy = y * sh + r - ph;
                             if (iy < 0 || iy >= H) continue;
@@ -162,4 +192,13 @@ int oracle_conv2d(const uint16_t *Wt, const uint8_t *mask, const uint16_t *in,
     }
     free(ind);
     return 0;
+}
+
+int oracle_conv2d(const uint16_t *Wt, const uint8_t *mask, const uint16_t *in,
+                  int64_t B, int64_t Cin, int64_t H, int64_t Wd, int64_t Cout,
+                  int64_t R, int64_t Sk, int64_t sh, int64_t sw, int64_t ph, int64_t pw,
+                  int layout, double *out, double *scale)
+{
+    return oracle_conv2d_fmt(Wt, mask, in, B, Cin, H, Wd, Cout, R, Sk, sh, sw, ph, pw, layout,
+                             out, scale, 0);
 }

@@ -23,15 +23,41 @@ def kept_per_group(K, sparsity):
     return int(round(K * (1.0 - float(sparsity))))
 
 
-def _normal_f16(rng, shape, integer=False):
+def float32_to_bfloat16_bits(a):
+    """Round float32 to bfloat16 (nearest, ties to even); uint16 bit patterns.
+    numpy has no bfloat16 dtype, so such tensors travel as uint16 arrays."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    rounded = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    out = (rounded >> np.uint32(16)).astype(np.uint16)
+    nan = np.isnan(a)
+    if nan.any():
+        out[nan] = 0x7FC0
+    return out
+
+
+def bfloat16_bits_to_float32(b):
+    """Exact widening of bfloat16 bit patterns (uint16) to float32."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def as_float(a):
+    """float view of a host tensor of either format (float16 array, or uint16
+    array of bfloat16 bits) for code that needs numbers, not bits."""
+    return bfloat16_bits_to_float32(a) if a.dtype == np.uint16 else a
+
+
+def _normal_f16(rng, shape, integer=False, fmt="f16"):
+    """N(0,1) drawn in float32 and rounded to the 16-bit format (or small
+    integers, exact in both formats).  fmt "bf16" returns uint16 bit patterns."""
+    narrow = (lambda v: v.astype(np.float16)) if fmt == "f16" else float32_to_bfloat16_bits
     if integer:
-        return rng.integers(-4, 5, size=shape).astype(np.float16)
-    out = np.empty(shape, dtype=np.float16)
+        return narrow(rng.integers(-4, 5, size=shape).astype(np.float32))
+    out = np.empty(shape, dtype=np.float16 if fmt == "f16" else np.uint16)
     flat = out.reshape(-1)
     step = 1 << 24
     for lo in range(0, flat.size, step):
         n = min(step, flat.size - lo)
-        flat[lo:lo + n] = rng.standard_normal(n, dtype=np.float32).astype(np.float16)
+        flat[lo:lo + n] = narrow(rng.standard_normal(n, dtype=np.float32))
     return out
 
 
@@ -41,10 +67,10 @@ class Problem:
     K: int
     N: int
     V: int
-    W: np.ndarray            # (M, K) float16, dense (not masked)
+    W: np.ndarray            # (M, K) float16 (or uint16 bfloat16 bits), dense (not masked)
     mask: np.ndarray         # (M, K) uint8
     perm: np.ndarray         # (M,) int32, perm[i] = original row of stored row i
-    X: np.ndarray            # (K, N) float16, or None for conv problems
+    X: np.ndarray            # (K, N) same format as W, or None for conv problems
     cols: list = field(default_factory=list)   # per group, ascending kept columns
     conv: dict = None        # conv geometry and the activation tensor, if any
 
@@ -71,13 +97,13 @@ def make_mask(rng, M, K, V, k_g, perm, ragged=False):
 
 
 def make_spmm(M, K, N, V, sparsity, seed, identity_perm=False, integer=False,
-              ragged=False, with_x=True):
+              ragged=False, with_x=True, fmt="f16"):
     """A linear-layer problem Y = (W . mask) X."""
     if M % V:
         raise ValueError("M %% V != 0")
     rng = np.random.Generator(np.random.PCG64(seed))
-    W = _normal_f16(rng, (M, K), integer)
-    X = _normal_f16(rng, (K, N), integer) if with_x else None
+    W = _normal_f16(rng, (M, K), integer, fmt)
+    X = _normal_f16(rng, (K, N), integer, fmt) if with_x else None
     perm = rng.permutation(M).astype(np.int32)
     if identity_perm:
         perm = np.arange(M, dtype=np.int32)
@@ -86,14 +112,14 @@ def make_spmm(M, K, N, V, sparsity, seed, identity_perm=False, integer=False,
 
 
 def make_conv(batch, Cin, H, Wd, Cout, R, S, V, sparsity, seed, stride=(1, 1),
-              pad=(0, 0), layout="NCHW", integer=False):
+              pad=(0, 0), layout="NCHW", integer=False, fmt="f16"):
     """A convolution problem in implicit-GEMM view: M = Cout, K = Cin*R*S
     with k = (c*R + r)*S + s, N = batch*Ho*Wo."""
     rng = np.random.Generator(np.random.PCG64(seed))
     K = Cin * R * S
-    W = _normal_f16(rng, (Cout, K), integer)
+    W = _normal_f16(rng, (Cout, K), integer, fmt)
     shape = (batch, Cin, H, Wd) if layout == "NCHW" else (Cin, H, Wd, batch)
-    inp = _normal_f16(rng, shape, integer)
+    inp = _normal_f16(rng, shape, integer, fmt)
     perm = rng.permutation(Cout).astype(np.int32)
     mask, cols = make_mask(rng, Cout, K, V, kept_per_group(K, sparsity), perm)
     Ho = (H + 2 * pad[0] - R) // stride[0] + 1

@@ -279,3 +279,68 @@ def test_conv_integer_exact_midsize():
     w = torch.from_numpy((p.W.astype(np.int64) * p.mask).reshape(32, 16, 3, 3).astype(np.float64))
     want = torch.nn.functional.conv2d(torch.from_numpy(inp.astype(np.float64)), w, padding=1).numpy()
     assert np.array_equal(got, want)
+
+
+# ----------------------------------------------------------------- bfloat16 operands
+def _bf16_to_f64_by_torch(bits):
+    """bfloat16 bit patterns widened by the library's own conversion."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).double().numpy()
+
+
+def test_bfloat16_decode_all_patterns_match_library():
+    bits = np.arange(65536, dtype=np.uint16)
+    want = _bf16_to_f64_by_torch(bits)
+    got = np.array([c_oracle.bfloat16_to_double(int(b)) for b in bits])
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+def test_bfloat16_decode_closed_forms():
+    assert c_oracle.bfloat16_to_double(0x3F80) == 1.0
+    assert c_oracle.bfloat16_to_double(0xC000) == -2.0
+    assert c_oracle.bfloat16_to_double(0x0001) == 2.0 ** -133     # smallest subnormal
+    assert c_oracle.bfloat16_to_double(0x0080) == 2.0 ** -126     # smallest normal
+    assert c_oracle.bfloat16_to_double(0x7F7F) == (2.0 - 2.0 ** -7) * 2.0 ** 127
+    assert c_oracle.bfloat16_to_double(0x7F80) == float("inf")
+
+
+def test_spmm_bfloat16_brute_force_and_definition():
+    p = synth.make_spmm(8, 10, 5, 4, 0.4, seed=31, fmt="bf16")
+    Wf, Xf = _bf16_to_f64_by_torch(p.W), _bf16_to_f64_by_torch(p.X)
+    Y, S = c_oracle.spmm(p.W, p.mask, p.X)
+    Yb, Sb = _brute_spmm(Wf, p.mask, Xf)
+    assert np.allclose(Y, Yb, rtol=1e-13, atol=0) and np.allclose(S, Sb, rtol=1e-13, atol=0)
+    q = synth.make_spmm(96, 80, 33, 32, 0.5, seed=32, fmt="bf16")
+    Y, S = c_oracle.spmm(q.W, q.mask, q.X)
+    Yd, Sd = definition.spmm(_bf16_to_f64_by_torch(q.W), q.mask, _bf16_to_f64_by_torch(q.X))
+    assert np.allclose(Y, Yd, rtol=1e-12, atol=1e-12) and np.allclose(S, Sd, rtol=1e-12, atol=1e-12)
+
+
+def test_spmm_bfloat16_integer_inputs_equal_the_binary16_result():
+    """Small integers are exact in both formats, so the two formats' oracles
+    must give the same numbers bit for bit (same seed, same draws)."""
+    a = synth.make_spmm(64, 48, 20, 32, 0.5, seed=33, integer=True)
+    b = synth.make_spmm(64, 48, 20, 32, 0.5, seed=33, integer=True, fmt="bf16")
+    assert np.array_equal(a.mask, b.mask)
+    Ya, _ = c_oracle.spmm(a.W, a.mask, a.X)
+    Yb, _ = c_oracle.spmm(b.W, b.mask, b.X)
+    assert np.array_equal(Ya, Yb)
+
+
+def test_conv_bfloat16_matches_library_conv2d_float64():
+    p = synth.make_conv(2, 6, 7, 5, 8, 3, 3, 4, 0.5, seed=34, stride=(2, 1), pad=(1, 1), fmt="bf16")
+    g = p.conv
+    got, _ = c_oracle.conv2d(p.W, p.mask, g["input"], 3, 3, (2, 1), (1, 1))
+    Wm = torch.from_numpy(_bf16_to_f64_by_torch(p.W) * p.mask).reshape(8, 6, 3, 3)
+    want = torch.nn.functional.conv2d(torch.from_numpy(_bf16_to_f64_by_torch(g["input"])), Wm,
+                                      stride=(2, 1), padding=(1, 1)).numpy()
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_bfloat16_rounding_of_the_generator_matches_library():
+    a = np.random.default_rng(5).standard_normal(50000).astype(np.float32)
+    bits = synth.float32_to_bfloat16_bits(a)
+    want = torch.from_numpy(a).to(torch.bfloat16)
+    assert np.array_equal(bits.view(np.int16), want.view(torch.int16).numpy())
