@@ -16,6 +16,8 @@ Prints ONE JSON line.  value = useful TFLOP/s = 2*nnz*N / t.
 """
 import argparse
 import json
+
+import numpy as np
 import os
 import sys
 import time
@@ -49,11 +51,16 @@ class Case:
         self.A.set_tuning(kernel, tile_n)
         self.A.bind_device("cuda:0")
         self.info = self.A.info()
-        x0 = torch.from_numpy(p.X).to("cuda:0")
+        if p.X.dtype == np.uint16:   # bfloat16 bit patterns
+            x0 = torch.from_numpy(p.X.view(np.int16)).view(torch.bfloat16).to("cuda:0")
+            if out_dtype == "float16":
+                out_dtype = "bfloat16"
+        else:
+            x0 = torch.from_numpy(p.X).to("cuda:0")
         self.X = [x0] + [x0.clone() for _ in range(rotate - 1)]
         dt = getattr(torch, out_dtype)
         self.Y = [torch.empty((p.M, p.N), dtype=dt, device="cuda:0") for _ in range(rotate)]
-        self.out_bytes = 2 if out_dtype == "float16" else 4
+        self.out_bytes = 4 if out_dtype == "float32" else 2
         self.i = 0
 
     def step(self):
@@ -217,6 +224,8 @@ def main():
     conv_dense = measure_conv(synth.config(3, sparsity=0.0), max(10, args.steps // 4), max(3, args.warmup // 4))
     conv_r["speedup_vs_own_dense"] = conv_dense["ms"] / conv_r["ms"]
     conv_r["dense_ms"] = conv_dense["ms"]
+    bf16_r = measure_spmm(synth.config(1, fmt="bf16"), args.steps, args.warmup, cold=True,
+                          tile_n=args.tile_n, kernel=args.kernel)
     lib_r = measure_library_gemm(p, args.steps, args.warmup)
     lib_r["sparse_speedup_over_library_dense"] = lib_r["ms"] / main_r["ms"]
 
@@ -243,6 +252,7 @@ def main():
         "warm_cache": {"ms": warm_r["ms"], "tflops": warm_r["tflops"]},
         "identity_perm": {"ms": ident_r["ms"], "shuffled_over_identity": main_r["ms"] / ident_r["ms"]},
         "conv2d_config4": conv_r,
+        "bf16_operands": {"ms": bf16_r["ms"], "tflops": bf16_r["tflops"]},
         "library_dense_gemm": lib_r,
         "cpu_baseline": cpu,
         "context": PAPER_CONTEXT,

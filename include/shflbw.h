@@ -45,8 +45,9 @@ extern "C" {
 typedef struct shflbw_matrix shflbw_matrix; /* opaque; owns host copies of the packed arrays */
 
 typedef enum {
-    SHFLBW_F16 = 0, /* IEEE binary16 */
-    SHFLBW_F32 = 2  /* IEEE binary32 (output only) */
+    SHFLBW_F16 = 0,  /* IEEE binary16 */
+    SHFLBW_BF16 = 1, /* bfloat16 */
+    SHFLBW_F32 = 2   /* IEEE binary32 (output only) */
 } shflbw_dtype;
 
 typedef enum {
@@ -73,7 +74,9 @@ typedef enum {
  * indices, and store the kept V x 1 vectors stitched into V x T_K tiles in
  * the order the matrix cores consume them.
  *
- *  W     host, M x K binary16, row-major, leading dimension ldw >= K (elements).
+ *  W     host, M x K of wdtype (SHFLBW_F16 or SHFLBW_BF16; 16-bit patterns), row-major,
+ *        leading dimension ldw >= K (elements).  The activations given to
+ *        shflbw_spmm / shflbw_conv2d later must have the same type.
  *  mask  host, M x K bytes, row-major, leading dimension K; non-zero = kept.
  *        NULL: a V x 1 vector is kept iff any of its V weights is non-zero.
  *        Kept weights whose value is zero are stored like any other.
@@ -123,8 +126,8 @@ int shflbw_set_tuning(shflbw_matrix* A, int kernel, int tile_n);
 /*
  * Linear layer (Algorithm 1: BulkLoadMeta / StitchTile / WarpMMA loop, then
  * ReorderedWriteBack):  Y = (W .* mask) X.
- *  X  device, K x N binary16, row-major, leading dimension ldx >= N.
- *  Y  device, M x N of ydtype (SHFLBW_F16 or SHFLBW_F32), leading dimension
+ *  X  device, K x N of the matrix's wdtype, row-major, leading dimension ldx >= N.
+ *  Y  device, M x N of ydtype (the matrix's wdtype, or SHFLBW_F32), leading dimension
  *     ldy >= N.  Must not overlap X.
  * N == 0 is a no-op.  Groups without kept columns produce zero rows.
  * Fast path: N, ldx, ldy multiples of 8 and 16-byte aligned bases; other
@@ -138,8 +141,8 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
  * exists only in on-chip buffers.  A has M = C_out rows and K = C_in*R*S
  * columns flattened as k = (c*R + r)*S + s.  Cross-correlation (no kernel
  * flip), zero padding, dilation 1, groups 1.
- *  in   device, binary16: [batch][C_in][H][W] (NCHW) or [C_in][H][W][batch] (CHWN).
- *  out  device, ydtype:   [batch][C_out][H_out][W_out] or [C_out][H_out][W_out][batch],
+ *  in   device, the matrix's wdtype: [batch][C_in][H][W] (NCHW) or [C_in][H][W][batch] (CHWN).
+ *  out  device, ydtype (the matrix's wdtype, or SHFLBW_F32): [batch][C_out][H_out][W_out] or [C_out][H_out][W_out][batch],
  *       H_out = (H + 2*pad_h - R)/stride_h + 1, W_out likewise.
  * For V = 32 and 64 a workgroup copies the part of the input its output
  * positions can touch into LDS once and gathers from there; other V, and

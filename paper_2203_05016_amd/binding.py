@@ -12,7 +12,7 @@ import os
 
 import numpy as np
 
-F16, F32 = 0, 2
+F16, BF16, F32 = 0, 1, 2
 NCHW, CHWN = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -100,18 +100,25 @@ def _ydtype(t):
     import torch
     if t.dtype == torch.float16:
         return F16
+    if t.dtype == torch.bfloat16:
+        return BF16
     if t.dtype == torch.float32:
         return F32
-    raise TypeError("output tensor must be float16 or float32")
+    raise TypeError("output tensor must be float16, bfloat16 or float32")
 
 
 class Matrix:
     """Owner of one ``shflbw_matrix`` handle and, once bound, of the device
     buffer (a torch uint8 tensor) that holds its packed arrays."""
 
-    def __init__(self, handle):
+    def __init__(self, handle, bf16=False):
         self._h = handle
         self._dev = None
+        self.bf16 = bf16   # operand format: bfloat16 instead of float16
+
+    def _operand_dtype(self):
+        import torch
+        return torch.bfloat16 if self.bf16 else torch.float16
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
@@ -141,7 +148,7 @@ class Matrix:
     def decompress(self, ldw=None):
         i = self.info()
         ldw = i["K"] if ldw is None else ldw
-        out = np.zeros((i["M"], ldw), dtype=np.float16)
+        out = np.zeros((i["M"], ldw), dtype=np.uint16 if self.bf16 else np.float16)
         _check(lib().shflbw_decompress(self._h, _host_ptr(out), ldw))
         return out
 
@@ -161,13 +168,14 @@ class Matrix:
         return self
 
     def spmm(self, X, Y=None, out_dtype=None, stream=None):
-        """Y = (W . mask) X for a device tensor X of shape (K, N), float16."""
+        """Y = (W . mask) X for a device tensor X of shape (K, N) in the
+        matrix's operand format (float16, or bfloat16)."""
         import torch
-        if X.dtype != torch.float16 or X.dim() != 2 or X.stride(1) != 1 and X.shape[1] > 1:
-            raise TypeError("X must be a 2-D float16 tensor with unit column stride")
+        if X.dtype != self._operand_dtype() or X.dim() != 2 or X.stride(1) != 1 and X.shape[1] > 1:
+            raise TypeError("X must be a 2-D %s tensor with unit column stride" % self._operand_dtype())
         N = X.shape[1]
         if Y is None:
-            Y = torch.empty((self.info()["M"], N), dtype=out_dtype or torch.float16,
+            Y = torch.empty((self.info()["M"], N), dtype=out_dtype or self._operand_dtype(),
                             device=X.device)
         ldx = X.stride(0) if X.shape[0] > 1 else max(N, 1)
         ldy = Y.stride(0) if Y.shape[0] > 1 else max(N, 1)
@@ -178,10 +186,10 @@ class Matrix:
 
     def conv2d(self, inp, R, S, stride=(1, 1), pad=(0, 0), layout="NCHW", out=None,
                out_dtype=None, stream=None):
-        """Masked conv2d of a contiguous float16 device tensor."""
+        """Masked conv2d of a contiguous device tensor in the matrix's operand format."""
         import torch
-        if inp.dtype != torch.float16 or not inp.is_contiguous():
-            raise TypeError("input must be a contiguous float16 tensor")
+        if inp.dtype != self._operand_dtype() or not inp.is_contiguous():
+            raise TypeError("input must be a contiguous %s tensor" % self._operand_dtype())
         if layout == "NCHW":
             B, C, H, W = inp.shape
         else:
@@ -191,7 +199,7 @@ class Matrix:
         Cout = self.info()["M"]
         shape = (B, Cout, Ho, Wo) if layout == "NCHW" else (Cout, Ho, Wo, B)
         if out is None:
-            out = torch.empty(shape, dtype=out_dtype or torch.float16, device=inp.device)
+            out = torch.empty(shape, dtype=out_dtype or self._operand_dtype(), device=inp.device)
         _check(lib().shflbw_conv2d(self._h, ctypes.c_void_p(inp.data_ptr()),
                                    ctypes.c_void_p(out.data_ptr()), B, C, H, W, R, S,
                                    stride[0], stride[1], pad[0], pad[1],
@@ -201,11 +209,13 @@ class Matrix:
 
 
 def compress(W, mask, perm, V, K=None):
-    """shflbw_compress on numpy arrays: W (M, ldw) float16 of which the first K
+    """shflbw_compress on numpy arrays: W (M, ldw) float16, or uint16 holding
+    bfloat16 bit patterns (numpy has no such dtype), of which the first K
     columns are the matrix (default: all), mask (M, K) uint8 or None, perm
     (M,) int32 or None."""
-    if W.dtype != np.float16 or W.ndim != 2:
-        raise TypeError("W must be a 2-D float16 array")
+    if W.dtype not in (np.float16, np.uint16) or W.ndim != 2:
+        raise TypeError("W must be a 2-D float16 array, or uint16 holding bfloat16 bits")
+    bf16 = W.dtype == np.uint16
     W = np.ascontiguousarray(W)
     M, ldw = W.shape
     K = ldw if K is None else K
@@ -216,6 +226,6 @@ def compress(W, mask, perm, V, K=None):
     if p is not None and p.shape != (M,):
         raise ValueError("perm shape")
     h = ctypes.c_void_p()
-    _check(lib().shflbw_compress(_host_ptr(W), ldw, _host_ptr(m), _host_ptr(p), M, K, V, F16,
-                                 ctypes.byref(h)))
-    return Matrix(h)
+    _check(lib().shflbw_compress(_host_ptr(W), ldw, _host_ptr(m), _host_ptr(p), M, K, V,
+                                 BF16 if bf16 else F16, ctypes.byref(h)))
+    return Matrix(h, bf16)

@@ -31,7 +31,7 @@ PackedView view_of(const shflbw_matrix* A)
     return v;
 }
 
-template <int V, int GW, typename OutT>
+template <int V, int GW, typename OutT, bool BF>
 int launch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long ldy, long N,
                 hipStream_t stream)
 {
@@ -47,26 +47,26 @@ int launch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long l
     a.gblocks = (A->G + GW - 1) / GW;
     const long wgs = ((n_tiles + 7) / 8) * 8 * a.gblocks;
     if (wgs > 0x7fffffffL) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
-    hipLaunchKernelGGL((shflbw_slab_kernel<V, GW, OutT>), dim3((unsigned)wgs), dim3(64 * (GW + SLAB_LOADERS)), 0,
+    hipLaunchKernelGGL((shflbw_slab_kernel<V, GW, OutT, BF>), dim3((unsigned)wgs), dim3(64 * (GW + SLAB_LOADERS)), 0,
                        stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
     return SHFLBW_OK;
 }
 
-template <typename OutT>
+template <typename OutT, bool BF>
 int dispatch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long ldy, long N,
                   hipStream_t stream)
 {
     switch (A->V) {
-        case 16: return launch_slab<16, 12, OutT>(A, X, ldx, Y, ldy, N, stream);
-        case 32: return launch_slab<32, 12, OutT>(A, X, ldx, Y, ldy, N, stream);
-        case 64: return launch_slab<64, 8, OutT>(A, X, ldx, Y, ldy, N, stream);
+        case 16: return launch_slab<16, 12, OutT, BF>(A, X, ldx, Y, ldy, N, stream);
+        case 32: return launch_slab<32, 12, OutT, BF>(A, X, ldx, Y, ldy, N, stream);
+        case 64: return launch_slab<64, 8, OutT, BF>(A, X, ldx, Y, ldy, N, stream);
     }
     return fail(SHFLBW_ERR_BAD_OPTION, "the slab kernel supports V = 16, 32, 64");
 }
 
-template <int V, int WN, typename OutT, class Geom>
+template <int V, int WN, typename OutT, class Geom, bool BF>
 int launch_gather(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t stream)
 {
     constexpr int WAVES = 4, PD = 2;
@@ -74,41 +74,55 @@ int launch_gather(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t 
     const long gx = (n_tiles + WAVES - 1) / WAVES;
     if (gx > 0x7fffffffL || A->G > 65535) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
     dim3 grid((unsigned)gx, (unsigned)A->G, 1), block(64 * WAVES, 1, 1);
-    hipLaunchKernelGGL((shflbw_gather_kernel<V, WN, WAVES, PD, OutT, Geom>), grid, block, 0, stream,
+    hipLaunchKernelGGL((shflbw_gather_kernel<V, WN, WAVES, PD, OutT, Geom, BF>), grid, block, 0, stream,
                        view_of(A), geom, (int)n_tiles);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
     return SHFLBW_OK;
 }
 
-template <int V, typename OutT, class Geom>
+template <int V, typename OutT, class Geom, bool BF>
 int dispatch_wn(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t stream)
 {
     int wn = A->tune_tile_n;
     if (wn == 0) wn = (V >= 128) ? 64 : 128;
     if (V >= 128 && wn == 128) wn = 64;  // 4 row blocks x 4 tiles of accumulators do not fit
-    if (wn == 64) return launch_gather<V, 64, OutT, Geom>(A, geom, N, stream);
-    return launch_gather<(V >= 128 ? 64 : V), 128, OutT, Geom>(A, geom, N, stream);
+    if (wn == 64) return launch_gather<V, 64, OutT, Geom, BF>(A, geom, N, stream);
+    return launch_gather<(V >= 128 ? 64 : V), 128, OutT, Geom, BF>(A, geom, N, stream);
 }
 
-template <typename OutT, class Geom>
+template <typename OutT, class Geom, bool BF>
 int dispatch_v(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t stream)
 {
     switch (A->V) {
-        case 16: return dispatch_wn<16, OutT, Geom>(A, geom, N, stream);
-        case 32: return dispatch_wn<32, OutT, Geom>(A, geom, N, stream);
-        case 64: return dispatch_wn<64, OutT, Geom>(A, geom, N, stream);
-        case 128: return dispatch_wn<128, OutT, Geom>(A, geom, N, stream);
+        case 16: return dispatch_wn<16, OutT, Geom, BF>(A, geom, N, stream);
+        case 32: return dispatch_wn<32, OutT, Geom, BF>(A, geom, N, stream);
+        case 64: return dispatch_wn<64, OutT, Geom, BF>(A, geom, N, stream);
+        case 128: return dispatch_wn<128, OutT, Geom, BF>(A, geom, N, stream);
     }
     return fail(SHFLBW_ERR_BAD_SHAPE, "unsupported V");
 }
 
+// Output type by the matrix's operand format: the same 16-bit format, or fp32.
 template <class Geom>
 int dispatch_out(const shflbw_matrix* A, const Geom& geom, long N, shflbw_dtype ydtype,
                  hipStream_t stream)
 {
-    if (ydtype == SHFLBW_F16) return dispatch_v<_Float16, Geom>(A, geom, N, stream);
-    return dispatch_v<float, Geom>(A, geom, N, stream);
+    if (A->dtype == SHFLBW_BF16) {
+        if (ydtype == SHFLBW_BF16) return dispatch_v<__bf16, Geom, true>(A, geom, N, stream);
+        return dispatch_v<float, Geom, true>(A, geom, N, stream);
+    }
+    if (ydtype == SHFLBW_F16) return dispatch_v<_Float16, Geom, false>(A, geom, N, stream);
+    return dispatch_v<float, Geom, false>(A, geom, N, stream);
+}
+
+// ydtype must be the operand format of the matrix or fp32
+int check_ydtype(const shflbw_matrix* A, shflbw_dtype ydtype)
+{
+    if (ydtype == SHFLBW_F32 || (int)ydtype == A->dtype) return SHFLBW_OK;
+    return fail(SHFLBW_ERR_BAD_DTYPE, A->dtype == SHFLBW_BF16
+                    ? "ydtype must be SHFLBW_BF16 or SHFLBW_F32 for a bfloat16 matrix"
+                    : "ydtype must be SHFLBW_F16 or SHFLBW_F32 for a binary16 matrix");
 }
 
 // Picks the box of output positions one workgroup of the staged convolution
@@ -192,28 +206,47 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     return true;
 }
 
-template <int V, int NT, typename OutT>
+template <int V, int NT, typename OutT, bool BF>
 int launch_conv_nt(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStream_t stream)
 {
     a.A = view_of(A);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shflbw_conv_kernel<V, NT, OutT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shflbw_conv_kernel<V, NT, OutT, BF>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
     const long wgs = (long)a.nb * a.ny * a.nx * a.gblocks;
-    hipLaunchKernelGGL((shflbw_conv_kernel<V, NT, OutT>), dim3((unsigned)wgs), dim3(64 * CONV_GW), lds_bytes,
+    hipLaunchKernelGGL((shflbw_conv_kernel<V, NT, OutT, BF>), dim3((unsigned)wgs), dim3(64 * CONV_GW), lds_bytes,
                        stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
     return SHFLBW_OK;
 }
 
-template <int V, typename OutT>
+template <int V, typename OutT, bool BF>
 int launch_conv(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStream_t stream)
 {
     const int npos = a.tb * a.th * a.tw;
-    if (npos <= 32) return launch_conv_nt<V, 1, OutT>(A, a, lds_bytes, stream);
-    if (npos <= 64) return launch_conv_nt<V, 2, OutT>(A, a, lds_bytes, stream);
-    return launch_conv_nt<V, 4, OutT>(A, a, lds_bytes, stream);
+    if (npos <= 32) return launch_conv_nt<V, 1, OutT, BF>(A, a, lds_bytes, stream);
+    if (npos <= 64) return launch_conv_nt<V, 2, OutT, BF>(A, a, lds_bytes, stream);
+    return launch_conv_nt<V, 4, OutT, BF>(A, a, lds_bytes, stream);
+}
+
+template <int V>
+int dispatch_conv_v(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, shflbw_dtype ydtype,
+                    hipStream_t stream)
+{
+    if (A->dtype == SHFLBW_BF16) {
+        if (ydtype == SHFLBW_BF16) return launch_conv<V, __bf16, true>(A, a, lds_bytes, stream);
+        return launch_conv<V, float, true>(A, a, lds_bytes, stream);
+    }
+    if (ydtype == SHFLBW_F16) return launch_conv<V, _Float16, false>(A, a, lds_bytes, stream);
+    return launch_conv<V, float, false>(A, a, lds_bytes, stream);
+}
+
+int dispatch_conv(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, shflbw_dtype ydtype,
+                  hipStream_t stream)
+{
+    if (A->V == 32) return dispatch_conv_v<32>(A, a, lds_bytes, ydtype, stream);
+    return dispatch_conv_v<64>(A, a, lds_bytes, ydtype, stream);
 }
 
 int check_bound(const shflbw_matrix* A)
@@ -259,8 +292,7 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
 {
     using namespace shflbw;
     if (!A) return fail(SHFLBW_ERR_NULL_ARG, "A is NULL");
-    if (ydtype != SHFLBW_F16 && ydtype != SHFLBW_F32)
-        return fail(SHFLBW_ERR_BAD_DTYPE, "ydtype must be SHFLBW_F16 or SHFLBW_F32");
+    if (int rcd = check_ydtype(A, ydtype)) return rcd;
     if (N < 0) return fail(SHFLBW_ERR_BAD_SHAPE, "N < 0");
     if (N == 0) return SHFLBW_OK;
     if (!X || !Y) return fail(SHFLBW_ERR_NULL_ARG, "X and Y must not be NULL");
@@ -288,8 +320,14 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
         use_slab = A->G >= gw && density >= need;
     }
     if (use_slab) {
-        if (ydtype == SHFLBW_F16) return dispatch_slab<_Float16>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);
-        return dispatch_slab<float>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);
+        if (A->dtype == SHFLBW_BF16) {
+            if (ydtype == SHFLBW_BF16)
+                return dispatch_slab<__bf16, true>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);
+            return dispatch_slab<float, true>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);
+        }
+        if (ydtype == SHFLBW_F16)
+            return dispatch_slab<_Float16, false>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);
+        return dispatch_slab<float, false>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);
     }
     if (aligned) {
         GeomLinear<true> g{static_cast<const _Float16*>(X), Y, (long)ldx, (long)ldy, (long)N};
@@ -305,8 +343,7 @@ int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, 
 {
     using namespace shflbw;
     if (!A) return fail(SHFLBW_ERR_NULL_ARG, "A is NULL");
-    if (ydtype != SHFLBW_F16 && ydtype != SHFLBW_F32)
-        return fail(SHFLBW_ERR_BAD_DTYPE, "ydtype must be SHFLBW_F16 or SHFLBW_F32");
+    if (int rcd = check_ydtype(A, ydtype)) return rcd;
     if (layout != SHFLBW_NCHW && layout != SHFLBW_CHWN)
         return fail(SHFLBW_ERR_BAD_SHAPE, "unknown layout");
     if (batch < 0 || C_in <= 0 || H <= 0 || W <= 0 || R <= 0 || S <= 0 || stride_h <= 0 ||
@@ -350,11 +387,7 @@ int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, 
             const size_t lds_bytes = last_lds;
             ca.in = static_cast<const _Float16*>(in);
             ca.out = out;
-            if (A->V == 32)
-                return ydtype == SHFLBW_F16 ? launch_conv<32, _Float16>(A, ca, lds_bytes, st)
-                                            : launch_conv<32, float>(A, ca, lds_bytes, st);
-            return ydtype == SHFLBW_F16 ? launch_conv<64, _Float16>(A, ca, lds_bytes, st)
-                                        : launch_conv<64, float>(A, ca, lds_bytes, st);
+            return dispatch_conv(A, ca, lds_bytes, ydtype, st);
         }
         if (A->tune_kernel == 2)
             return fail(SHFLBW_ERR_BAD_OPTION,

@@ -62,7 +62,8 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
     using shflbw::fail;
     if (!W || !out) return fail(SHFLBW_ERR_NULL_ARG, "W and out must not be NULL");
     *out = nullptr;
-    if (wdtype != SHFLBW_F16) return fail(SHFLBW_ERR_BAD_DTYPE, "weights must be SHFLBW_F16");
+    if (wdtype != SHFLBW_F16 && wdtype != SHFLBW_BF16)
+        return fail(SHFLBW_ERR_BAD_DTYPE, "weights must be SHFLBW_F16 or SHFLBW_BF16");
     if (V != 16 && V != 32 && V != 64 && V != 128)
         return fail(SHFLBW_ERR_BAD_SHAPE, "V must be 16, 32, 64 or 128");
     if (M <= 0 || K <= 0) return fail(SHFLBW_ERR_BAD_SHAPE, "M and K must be positive");
@@ -74,6 +75,7 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
         shflbw_matrix* A = new shflbw_matrix();
         struct Guard { shflbw_matrix* p; ~Guard() { delete p; } } guard{A};
         A->M = M; A->K = K; A->V = V; A->G = M / V;
+        A->dtype = (int)wdtype;
         A->TK = (V == 16) ? 32 : 16;
         const int TK = A->TK, G = A->G;
 

@@ -60,7 +60,7 @@ struct ConvArgs {
 };
 
 // NT: 32-position instruction tiles per box (1, 2 or 4; a box holds at most 32*NT positions).
-template <int V, int NT, typename OutT>
+template <int V, int NT, typename OutT, bool BF>
 __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
 {
     constexpr int RB = V / 32;
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
                     for (int t = 0; t < NT; ++t)
 #pragma unroll
                         for (int rb = 0; rb < RB; ++rb)
-                            acc[rb][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x_cur[t], w[u][rb], acc[rb][t], 0, 0, 0);
+                            acc[rb][t] = mma32<BF>(x_cur[t], w[u][rb], acc[rb][t]);
                     const int sn = s + CONV_PD < nsteps ? s + CONV_PD : last;
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb) w[u][rb] = valp[((long)sn * RB + rb) * 64];

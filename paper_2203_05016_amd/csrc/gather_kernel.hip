@@ -48,6 +48,29 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// The matrix-core products.  Operands travel as 16-bit patterns in half8
+// registers whatever their format; BF selects the bfloat16 instruction, whose
+// operand and accumulator lane maps are those of the binary16 one.
+template <bool BF>
+__device__ __forceinline__ floatx16 mma32(half8 a, half8 b, floatx16 c)
+{
+    if constexpr (BF)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+template <bool BF>
+__device__ __forceinline__ floatx4 mma16(half8 a, half8 b, floatx4 c)
+{
+    if constexpr (BF)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
 
 // Orders LDS traffic between the lanes of one wavefront.  The hardware runs a
 // wavefront's LDS instructions in order; this only stops the compiler from
@@ -215,7 +238,7 @@ struct GatherShape {
     static constexpr int REGION = (2 * STAGE > EPI) ? 2 * STAGE : EPI;
 };
 
-template <int V, int WN, int WAVES, int PD, typename OutT, class Geom>
+template <int V, int WN, int WAVES, int PD, typename OutT, class Geom, bool BF>
 __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A, Geom geom,
                                                                   int n_tiles)
 {
@@ -330,11 +353,11 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
                 half4 l4 = __builtin_bit_cast(half4, lo), h4 = __builtin_bit_cast(half4, hi);
                 half8 a = {l4[0], l4[1], l4[2], l4[3], h4[0], h4[1], h4[2], h4[3]};
                 if (S::SMALL) {
-                    acc16[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wcur[0], acc16[t], 0, 0, 0);
+                    acc16[t] = mma16<BF>(a, wcur[0], acc16[t]);
                 } else {
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb)
-                        acc32[rb][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, wcur[rb], acc32[rb][t], 0, 0, 0);
+                        acc32[rb][t] = mma32<BF>(a, wcur[rb], acc32[rb][t]);
                 }
             }
             // no second sync: the next step writes the other buffer, and its own

@@ -56,6 +56,7 @@ struct shflbw_matrix {
     int dev_id = -1;
 
     int tune_kernel = 0, tune_tile_n = 0;
+    int dtype = 0;                     // SHFLBW_F16 or SHFLBW_BF16: format of the values and of the activations
 
     int total_steps() const { return step_ptr.empty() ? 0 : step_ptr.back(); }
 };

@@ -89,7 +89,7 @@ struct SlabArgs {
     int n_tiles, gblocks;     // 128-column tiles, blocks of GW groups
 };
 
-template <int V, int GW, typename OutT>
+template <int V, int GW, typename OutT, bool BF>
 __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(SlabArgs a)
 {
     constexpr bool SMALL = (V == 16);
@@ -288,11 +288,11 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 if (SMALL) {
-                    acc16[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x[t], mw[u][0], acc16[t], 0, 0, 0);
+                    acc16[t] = mma16<BF>(x[t], mw[u][0], acc16[t]);
                 } else {
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb)
-                        acc32[rb][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[t], mw[u][rb], acc32[rb][t], 0, 0, 0);
+                        acc32[rb][t] = mma32<BF>(x[t], mw[u][rb], acc32[rb][t]);
                 }
             }
             {

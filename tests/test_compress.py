@@ -151,3 +151,20 @@ def test_device_calls_validate_before_touching_the_gpu():
     assert L.shflbw_bind_device(A._h, ctypes.c_void_p(8), None) == -2           # misaligned
     assert L.shflbw_set_tuning(A._h, 5, 0) == -9 and L.shflbw_set_tuning(A._h, 0, 100) == -9
     assert L.shflbw_set_tuning(A._h, 1, 64) == 0
+
+
+def test_bfloat16_weights_round_trip_bitwise():
+    """bfloat16 weights travel as 16-bit patterns: same packing, same test hooks."""
+    p = synth.make_spmm(128, 200, 4, 32, 0.7, seed=9, fmt="bf16")
+    A = binding.compress(p.W, p.mask, p.perm, 32)
+    assert A.bf16
+    want = np.where(p.mask != 0, p.W, np.uint16(0))
+    got = A.decompress()
+    assert got.dtype == np.uint16 and np.array_equal(got, want)
+    # NULL mask: a vector is kept iff any weight is non-zero; -0 (0x8000) counts as zero
+    W = want.copy()
+    W[p.perm[:32], 5] = 0x8000
+    W[p.perm[:32], 6] = 0
+    B = binding.compress(W, None, p.perm, 32)
+    cols = B.group_columns(0)
+    assert 5 not in cols and 6 not in cols
