@@ -16,11 +16,11 @@ Prints ONE JSON line.  value = useful TFLOP/s = 2*nnz*N / t.
 """
 import argparse
 import json
-
-import numpy as np
 import os
 import sys
 import time
+
+import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
@@ -244,7 +244,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": MEASURED_TRAFFIC_BYTES,
                      "algorithmic_bytes_per_launch": main_r["bytes"],
-                     "kernel": "shflbw_slab_kernel<32,12,f16>"},
+                     "kernel": "shflbw_slab_kernel<32,12,_Float16,false>"},
         "mfma_peak_frac_useful": main_r["tflops"] * 1e12 / MFMA_F16_PEAK,
         "speedup_vs_own_dense": dense_r["ms"] / main_r["ms"],
         "dense_run": {"ms": dense_r["ms"], "tflops": dense_r["tflops"],
