@@ -149,3 +149,27 @@ def test_config3_attention_projection_sampled():
     Xs = np.ascontiguousarray(p.X[:, cols])
     Yr, S = c_oracle.spmm(p.W, p.mask, Xs)
     assert_within_scaled_tolerance(Y[:, cols], Yr, S, what="config3 sample")
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+def test_config5_large_layer_sampled(variant):
+    """Config 5 at full size (8192 x 8192 by 8192 x 16384, V = 64; sparsity
+    0 / 75 / 87.5 / 95 %), in the launch configuration the benchmark times
+    (automatic kernel choice): all rows on 256 sampled columns plus 64 sampled
+    full rows."""
+    import torch
+    from paper_2203_05016_amd import binding
+    from gpu_util import to_device, to_host
+    announce("config5", variant)
+    p = synth.config(4, variant=variant)
+    A = binding.compress(p.W, p.mask, p.perm, p.V).bind_device("cuda:0")
+    Y = to_host(A.spmm(to_device(p.X)))
+    rng = np.random.default_rng(500 + variant)
+    cols = np.sort(rng.choice(p.N, 256, replace=False))
+    Yr, S = c_oracle.spmm(p.W, p.mask, np.ascontiguousarray(p.X[:, cols]))
+    assert_within_scaled_tolerance(Y[:, cols], Yr, S, what="config5 columns")
+    rows = np.sort(rng.choice(p.M, 64, replace=False))
+    Yr, S = c_oracle.spmm(np.ascontiguousarray(p.W[rows]), np.ascontiguousarray(p.mask[rows]), p.X)
+    assert_within_scaled_tolerance(Y[rows], Yr, S, what="config5 rows")
+    del A, Y
+    torch.cuda.empty_cache()
