@@ -271,6 +271,12 @@ def main():
             r = measure_spmm(q, 10, 2, cold=True)
             extra["config5_s%.3f" % r["sparsity"]] = r
             del q
+        # matrix-vector-like regime (recurrent layers): few output columns
+        for (M, K, N, V, sp) in ((4096, 4096, 64, 32, 0.75), (4096, 1024, 128, 32, 0.75)):
+            q = synth.make_spmm(M, K, N, V, sp, seed=synth.BASE_SEED + 7000 + N)
+            r = measure_spmm(q, args.steps, args.warmup, cold=True)
+            r1 = measure_spmm(q, args.steps, args.warmup, cold=True, kernel=1)
+            extra["skinny_%dx%dx%d_s%.2f" % (M, K, N, sp)] = dict(r, whole_tile_gather_ms=r1["ms"])
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         with open(os.path.join(ROOT, "gpurun_out", "bench_all.json"), "w") as f:
             json.dump(extra, f, indent=1)

@@ -118,7 +118,9 @@ int shflbw_bind_device(shflbw_matrix* A, void* dev_buf, void* stream);
 /* Kernel selection, for measurement.  kernel: 0 = automatic, 1 = per-wave
  * gather kernel, 2 = shared-slab kernel for shflbw_spmm / staged kernel for
  * shflbw_conv2d (the call then fails with SHFLBW_ERR_BAD_OPTION when the
- * matrix, the operands or the shape do not allow it).
+ * matrix, the operands or the shape do not allow it), 3 = gather kernel with
+ * the k-steps of a tile split over the wavefronts of a workgroup (the variant
+ * for very few output columns; shflbw_conv2d treats 3 like 1).
  * tile_n: 0 = automatic, else the number of output columns one wavefront of
  * the gather kernel owns (64 or 128). */
 int shflbw_set_tuning(shflbw_matrix* A, int kernel, int tile_n);

@@ -66,29 +66,45 @@ int dispatch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long
     return fail(SHFLBW_ERR_BAD_OPTION, "the slab kernel supports V = 16, 32, 64");
 }
 
-template <int V, int WN, typename OutT, class Geom, bool BF>
+template <int V, int WN, typename OutT, class Geom, bool BF, bool SPLIT>
 int launch_gather(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t stream)
 {
     constexpr int WAVES = 4, PD = 2;
     const long n_tiles = (N + WN - 1) / WN;
-    const long gx = (n_tiles + WAVES - 1) / WAVES;
+    const long gx = SPLIT ? n_tiles : (n_tiles + WAVES - 1) / WAVES;
     if (gx > 0x7fffffffL || A->G > 65535) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
     dim3 grid((unsigned)gx, (unsigned)A->G, 1), block(64 * WAVES, 1, 1);
-    hipLaunchKernelGGL((shflbw_gather_kernel<V, WN, WAVES, PD, OutT, Geom, BF>), grid, block, 0, stream,
-                       view_of(A), geom, (int)n_tiles);
+    hipLaunchKernelGGL((shflbw_gather_kernel<V, WN, WAVES, PD, OutT, Geom, BF, SPLIT>), grid, block, 0,
+                       stream, view_of(A), geom, (int)n_tiles);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
     return SHFLBW_OK;
 }
 
+// Few column tiles (skinny N): the four wavefronts of a workgroup split the k-steps of
+// one tile instead of taking four tiles.  Linear layers only, 64-column tiles.
+template <class Geom> struct geom_can_split { static constexpr bool value = false; };
+template <bool AL> struct geom_can_split<GeomLinear<AL>> { static constexpr bool value = true; };
+
 template <int V, typename OutT, class Geom, bool BF>
 int dispatch_wn(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t stream)
 {
     int wn = A->tune_tile_n;
+    if constexpr (geom_can_split<Geom>::value) {
+        bool split = A->tune_kernel == 3;
+        if (A->tune_kernel == 0 && wn == 0) {
+            // automatic: split when whole tiles alone would leave most of the chip idle
+            // and the groups have enough k-steps to share out
+            const long waves = ((N + 63) / 64) * A->G;
+            const long steps = A->step_ptr.empty() ? 0 : A->step_ptr.back();
+            split = waves <= 512 && steps >= 8L * A->G;
+        }
+        if (split) return launch_gather<V, 64, OutT, Geom, BF, true>(A, geom, N, stream);
+    }
     if (wn == 0) wn = (V >= 128) ? 64 : 128;
     if (V >= 128 && wn == 128) wn = 64;  // 4 row blocks x 4 tiles of accumulators do not fit
-    if (wn == 64) return launch_gather<V, 64, OutT, Geom, BF>(A, geom, N, stream);
-    return launch_gather<(V >= 128 ? 64 : V), 128, OutT, Geom, BF>(A, geom, N, stream);
+    if (wn == 64) return launch_gather<V, 64, OutT, Geom, BF, false>(A, geom, N, stream);
+    return launch_gather<(V >= 128 ? 64 : V), 128, OutT, Geom, BF, false>(A, geom, N, stream);
 }
 
 template <typename OutT, class Geom, bool BF>
@@ -317,7 +333,9 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
         const long tiles = ((N + SLAB_TN - 1) / SLAB_TN) * ((A->G + gw - 1) / gw);
         const double density = (double)A->nnz / ((double)A->M * A->K);
         const double need = tiles >= 128 ? 0.11 : (A->V >= 64 ? 0.2 : 0.4);
-        use_slab = A->G >= gw && density >= need;
+        // very few column tiles: the gather kernel with split k-steps fills the chip better
+        const bool skinny = ((N + 63) / 64) * A->G <= 512;
+        use_slab = A->G >= gw && density >= need && !skinny;
     }
     if (use_slab) {
         if (A->dtype == SHFLBW_BF16) {
@@ -368,7 +386,7 @@ int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, 
     int rc = check_bound(A);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (A->tune_kernel != 1) {
+    if (A->tune_kernel != 1 && A->tune_kernel != 3) {
         // the plan depends on the matrix and the geometry only: keep the last one
         struct PlanKey { const shflbw_matrix* A; int64_t nnz; int v[14]; };
         static thread_local PlanKey last_key = {nullptr, 0, {0}};

@@ -291,7 +291,7 @@ size_t shflbw_device_bytes(const shflbw_matrix* A) { return A ? A->dev_bytes : 0
 int shflbw_set_tuning(shflbw_matrix* A, int kernel, int tile_n)
 {
     if (!A) return shflbw::fail(SHFLBW_ERR_NULL_ARG, "A is NULL");
-    if (kernel < 0 || kernel > 2) return shflbw::fail(SHFLBW_ERR_BAD_OPTION, "kernel must be 0, 1 or 2");
+    if (kernel < 0 || kernel > 3) return shflbw::fail(SHFLBW_ERR_BAD_OPTION, "kernel must be 0, 1, 2 or 3");
     if (tile_n != 0 && tile_n != 64 && tile_n != 128)
         return shflbw::fail(SHFLBW_ERR_BAD_OPTION, "tile_n must be 0, 64 or 128");
     A->tune_kernel = kernel;

@@ -238,25 +238,41 @@ struct GatherShape {
     static constexpr int REGION = (2 * STAGE > EPI) ? 2 * STAGE : EPI;
 };
 
-template <int V, int WN, int WAVES, int PD, typename OutT, class Geom, bool BF>
+// SPLIT = false: the wavefronts of a workgroup own different column tiles of one
+// group.  SPLIT = true (few column tiles, the matrix-vector-like regime of
+// recurrent layers): they share one tile, each takes a contiguous quarter of
+// the group's k-steps, and the partial accumulators are summed through LDS
+// before the first wavefront writes the tile back.
+template <int V, int WN, int WAVES, int PD, typename OutT, class Geom, bool BF, bool SPLIT>
 __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A, Geom geom,
                                                                   int n_tiles)
 {
     using S = GatherShape<V, WN>;
     constexpr int TK = S::TK, RB = S::RB, NT = S::NT, LPR = S::LPR, NLD = S::NLD;
     constexpr int PITCH = S::PITCH;
-    __shared__ __attribute__((aligned(16))) _Float16 smem[WAVES * S::REGION];
+    constexpr int ACC_REGS = S::SMALL ? NT * 4 : RB * NT * 16;       // fp32 accumulators per lane
+    constexpr int SPLIT_HALVES = SPLIT ? ACC_REGS * 64 * 2 : 0;      // LDS for one wavefront's partials
+    constexpr int SMEM_HALVES = WAVES * S::REGION > SPLIT_HALVES ? WAVES * S::REGION : SPLIT_HALVES;
+    __shared__ __attribute__((aligned(16))) _Float16 smem[SMEM_HALVES];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tile = blockIdx.x * WAVES + wave;
-    if (tile >= n_tiles) return;  // whole wavefront leaves; no workgroup barrier is used
+    const int tile = SPLIT ? (int)blockIdx.x : (int)blockIdx.x * WAVES + wave;
+    // without SPLIT a whole wavefront leaves and no workgroup barrier is used; with
+    // SPLIT the condition is the same for every wavefront of the workgroup
+    if (tile >= n_tiles) return;
     const int g = blockIdx.y;
     const long n0 = (long)tile * WN;
     _Float16* my = smem + wave * S::REGION;
 
-    const int sbeg = A.step_ptr[g];
-    const int nsteps = A.step_ptr[g + 1] - sbeg;
+    int sbeg = A.step_ptr[g];
+    int nsteps = A.step_ptr[g + 1] - sbeg;
+    if (SPLIT) {
+        const int first = (int)((long)nsteps * wave / WAVES);
+        const int end = (int)((long)nsteps * (wave + 1) / WAVES);
+        sbeg += first;
+        nsteps = end - first;
+    }
 
     // this lane's share of a staged tile: rows lrow..lrow+NLD-1, 8 columns at lcol
     const int lrow = (lane / LPR) * NLD;
@@ -365,6 +381,51 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
         }
     }
     SHFLBW_WAVE_LDS_SYNC();
+
+    if (SPLIT) {
+        // sum the partial accumulators into wavefront 0, one wavefront at a time;
+        // register r of lane l sits at float4 index (r/4)*64 + l, free of bank conflicts
+        floatx4* red = reinterpret_cast<floatx4*>(smem);
+        for (int w = WAVES - 1; w >= 1; --w) {
+            __syncthreads();   // the buffer (and, first time, every private region) is free
+            if (wave == w) {
+                if (S::SMALL) {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) red[t * 64 + lane] = acc16[t];
+                } else {
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int t = 0; t < NT; ++t)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                red[((rb * NT + t) * 4 + q) * 64 + lane] =
+                                    floatx4{acc32[rb][t][4 * q], acc32[rb][t][4 * q + 1],
+                                            acc32[rb][t][4 * q + 2], acc32[rb][t][4 * q + 3]};
+                }
+            }
+            __syncthreads();
+            if (wave == 0) {
+                if (S::SMALL) {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) acc16[t] += red[t * 64 + lane];
+                } else {
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int t = 0; t < NT; ++t)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const floatx4 v = red[((rb * NT + t) * 4 + q) * 64 + lane];
+                                acc32[rb][t][4 * q] += v[0]; acc32[rb][t][4 * q + 1] += v[1];
+                                acc32[rb][t][4 * q + 2] += v[2]; acc32[rb][t][4 * q + 3] += v[3];
+                            }
+                }
+            }
+        }
+        __syncthreads();       // wavefront 0 has read the last partials; its region is reused below
+        if (wave != 0) return;
+    }
 
     // ---- reordered write-back
     // Each pass moves ROWS_E stored rows x CW columns through LDS.  A lane

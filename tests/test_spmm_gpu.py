@@ -173,3 +173,49 @@ def test_config5_large_layer_sampled(variant):
     assert_within_scaled_tolerance(Y[rows], Yr, S, what="config5 rows")
     del A, Y
     torch.cuda.empty_cache()
+
+
+# ---------------------------------------------------------------- split k-steps (skinny N)
+@pytest.mark.parametrize("V", [16, 32, 64, 128])
+@pytest.mark.parametrize("N", [1, 16, 64, 130])
+def test_split_k_gather_kernel(V, N):
+    """Four wavefronts share one column tile and a quarter of the k-steps each."""
+    announce("split-k", V, N)
+    p = synth.make_spmm(3 * V, 777, N, V, 0.5, seed=601 + V + N)
+    Y = run_spmm(p, kernel=3)
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    assert_within_scaled_tolerance(Y, Yr, S, what="split-k")
+    assert_within_scaled_tolerance(run_spmm(p, kernel=3, out_dtype="float32"), Yr, S, what="split-k f32")
+
+
+def test_split_k_few_steps_empty_groups_and_integers():
+    announce("split-k edge cases")
+    # fewer k-steps than wavefronts, ragged and empty groups
+    p = synth.make_spmm(8 * 32, 40, 48, 32, 0.0, seed=611, ragged=True)
+    rows = p.perm[32:64]
+    p.mask[rows] = 0
+    p.cols[1] = np.zeros((0,), dtype=np.int64)
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    Y = run_spmm(p, kernel=3)
+    assert_within_scaled_tolerance(Y, Yr, S, what="split-k ragged")
+    assert not Y[rows].any()
+    # exact integers: the split changes the order of the sums, not the result
+    q = synth.make_spmm(128, 384, 40, 64, 0.5, seed=612, integer=True)
+    Yq, _ = c_oracle.spmm(q.W, q.mask, q.X)
+    assert np.array_equal(run_spmm(q, kernel=3, out_dtype="float32").astype(np.float64), Yq)
+    assert np.array_equal(run_spmm(q, kernel=3, out_dtype="float32"), run_spmm(q, kernel=1, out_dtype="float32"))
+    # bfloat16 operands
+    b = synth.make_spmm(128, 384, 40, 32, 0.5, seed=613, fmt="bf16")
+    Yb, Sb = c_oracle.spmm(b.W, b.mask, b.X)
+    assert_within_scaled_tolerance(run_spmm(b, kernel=3, out_dtype="float32"), Yb, Sb, what="split-k bf16")
+
+
+def test_skinny_shape_is_routed_to_split_k_and_matches():
+    """A recurrent-layer-like shape (4096 x 4096 weights, 64 columns): the
+    automatic choice, the split kernel and the plain gather kernel agree with
+    the oracle on all elements."""
+    announce("skinny auto")
+    p = synth.make_spmm(4096, 4096, 64, 32, 0.75, seed=614)
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    for kernel in (0, 3, 1):
+        assert_within_scaled_tolerance(run_spmm(p, kernel=kernel), Yr, S, what="skinny kernel %d" % kernel)
