@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libshflbw.so")
-SOURCES = ["compress.cpp", "api_device.hip"]
+SOURCES = ["compress.cpp", "api_device.hip", "launch_gather_f16.hip", "launch_gather_bf16.hip"]
 # packed fp32 instructions are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

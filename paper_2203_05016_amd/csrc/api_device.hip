@@ -10,6 +10,7 @@
 #include "slab_kernel.hip"
 #include "conv_kernel.hip"
 #include "shflbw_internal.h"
+#include "launch_gather.h"
 
 namespace shflbw {
 namespace {
@@ -66,70 +67,14 @@ int dispatch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long
     return fail(SHFLBW_ERR_BAD_OPTION, "the slab kernel supports V = 16, 32, 64");
 }
 
-template <int V, int WN, typename OutT, class Geom, bool BF, bool SPLIT>
-int launch_gather(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t stream)
-{
-    constexpr int WAVES = 4, PD = 2;
-    const long n_tiles = (N + WN - 1) / WN;
-    const long gx = SPLIT ? n_tiles : (n_tiles + WAVES - 1) / WAVES;
-    if (gx > 0x7fffffffL || A->G > 65535) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
-    dim3 grid((unsigned)gx, (unsigned)A->G, 1), block(64 * WAVES, 1, 1);
-    hipLaunchKernelGGL((shflbw_gather_kernel<V, WN, WAVES, PD, OutT, Geom, BF, SPLIT>), grid, block, 0,
-                       stream, view_of(A), geom, (int)n_tiles);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(e, "kernel launch");
-    return SHFLBW_OK;
-}
-
-// Few column tiles (skinny N): the four wavefronts of a workgroup split the k-steps of
-// one tile instead of taking four tiles.  Linear layers only, 64-column tiles.
-template <class Geom> struct geom_can_split { static constexpr bool value = false; };
-template <bool AL> struct geom_can_split<GeomLinear<AL>> { static constexpr bool value = true; };
-
-template <int V, typename OutT, class Geom, bool BF>
-int dispatch_wn(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t stream)
-{
-    int wn = A->tune_tile_n;
-    if constexpr (geom_can_split<Geom>::value) {
-        bool split = A->tune_kernel == 3;
-        if (A->tune_kernel == 0 && wn == 0) {
-            // automatic: split when whole tiles alone would leave most of the chip idle
-            // and the groups have enough k-steps to share out
-            const long waves = ((N + 63) / 64) * A->G;
-            const long steps = A->step_ptr.empty() ? 0 : A->step_ptr.back();
-            split = waves <= 512 && steps >= 8L * A->G;
-        }
-        if (split) return launch_gather<V, 64, OutT, Geom, BF, true>(A, geom, N, stream);
-    }
-    if (wn == 0) wn = (V >= 128) ? 64 : 128;
-    if (V >= 128 && wn == 128) wn = 64;  // 4 row blocks x 4 tiles of accumulators do not fit
-    if (wn == 64) return launch_gather<V, 64, OutT, Geom, BF, false>(A, geom, N, stream);
-    return launch_gather<(V >= 128 ? 64 : V), 128, OutT, Geom, BF, false>(A, geom, N, stream);
-}
-
-template <typename OutT, class Geom, bool BF>
-int dispatch_v(const shflbw_matrix* A, const Geom& geom, long N, hipStream_t stream)
-{
-    switch (A->V) {
-        case 16: return dispatch_wn<16, OutT, Geom, BF>(A, geom, N, stream);
-        case 32: return dispatch_wn<32, OutT, Geom, BF>(A, geom, N, stream);
-        case 64: return dispatch_wn<64, OutT, Geom, BF>(A, geom, N, stream);
-        case 128: return dispatch_wn<128, OutT, Geom, BF>(A, geom, N, stream);
-    }
-    return fail(SHFLBW_ERR_BAD_SHAPE, "unsupported V");
-}
-
-// Output type by the matrix's operand format: the same 16-bit format, or fp32.
+// The gather kernel's instantiations live in their own translation units, one per
+// operand format (launch_gather_f16.hip, launch_gather_bf16.hip).
 template <class Geom>
 int dispatch_out(const shflbw_matrix* A, const Geom& geom, long N, shflbw_dtype ydtype,
                  hipStream_t stream)
 {
-    if (A->dtype == SHFLBW_BF16) {
-        if (ydtype == SHFLBW_BF16) return dispatch_v<__bf16, Geom, true>(A, geom, N, stream);
-        return dispatch_v<float, Geom, true>(A, geom, N, stream);
-    }
-    if (ydtype == SHFLBW_F16) return dispatch_v<_Float16, Geom, false>(A, geom, N, stream);
-    return dispatch_v<float, Geom, false>(A, geom, N, stream);
+    if (A->dtype == SHFLBW_BF16) return run_gather_bf16(A, geom, N, ydtype, stream);
+    return run_gather_f16(A, geom, N, ydtype, stream);
 }
 
 // ydtype must be the operand format of the matrix or fp32
