@@ -27,6 +27,7 @@ sys.path.insert(0, ROOT)
 
 MFMA_F16_PEAK = 2.5166e15      # 256 CU x 4096 FLOP/clk x 2.4 GHz
 HBM_PEAK = 8.0e12
+L2_TO_CU_BYTES = 360.7e6        # 2.818e6 read requests of 128 B per launch of the headline kernel
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by the same counters on a 64 MiB copy (profiles/slab_kernel_ffn_config2_pmc.md)
 MEASURED_TRAFFIC_BYTES = 132.4e6
@@ -150,6 +151,37 @@ def measure_library_gemm(p, steps, warmup):
     return dict(ms=ms, dense_tflops=2.0 * p.M * p.K * p.N / (ms * 1e-3) / 1e12)
 
 
+def measure_l2_stream(p):
+    """The probe library's two streaming runs on the headline's X: the rate at which the
+    L2s can feed LDS with this access pattern when nothing else runs (hot), and with the
+    slab kernel's grid and sharing on cold operands."""
+    import ctypes
+    import torch
+    path = os.path.join(ROOT, "paper_2203_05016_amd", "libshflbw_probe.so")
+    lib = ctypes.CDLL(path)
+    fn = lib.shflbw_probe_l2_stream
+    fn.restype = ctypes.c_longlong
+    fn.argtypes = [ctypes.c_void_p, ctypes.c_longlong, ctypes.c_int, ctypes.c_longlong, ctypes.c_int,
+                   ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    rot = rotation_for(p)
+    Xs = [torch.from_numpy(p.X).to("cuda:0") for _ in range(rot)]
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    out = {}
+    for name, mode, passes, steps in (("hot", 0, 16, 20), ("kernel_pattern_cold", 1, 1, 100)):
+        state = {"i": 0, "bytes": 0}
+
+        def step():
+            x = Xs[state["i"] % rot]
+            state["bytes"] = fn(ctypes.c_void_p(x.data_ptr()), p.N, p.K, p.N, mode, 11, passes,
+                                ctypes.c_void_p(sink.data_ptr()), stream)
+            assert state["bytes"] > 0, "probe refused its arguments"
+            state["i"] += 1
+        ms = time_steps(step, steps, 5)
+        out[name] = {"ms": ms, "bytes": state["bytes"], "GBps": state["bytes"] / (ms * 1e-3) / 1e9}
+    return out
+
+
 def cpu_baseline(p):
     """The oracle as it stands, on the host cores, on the full headline
     workload (values only, no tolerance scale), best of two runs."""
@@ -226,6 +258,12 @@ def main():
     conv_r["dense_ms"] = conv_dense["ms"]
     bf16_r = measure_spmm(synth.config(1, fmt="bf16"), args.steps, args.warmup, cold=True,
                           tile_n=args.tile_n, kernel=args.kernel)
+    l2_r = measure_l2_stream(p)
+    # bytes the headline kernel pulls from the L2s into its CUs per launch (TCP_TCC_READ_REQ x 128 B,
+    # profiles/slab_kernel_ffn_config2_pmc.md) over its launch time, against the probe's rates
+    l2_r["kernel_l2_bytes_per_launch"] = L2_TO_CU_BYTES
+    l2_r["kernel_l2_GBps"] = L2_TO_CU_BYTES / (main_r["ms"] * 1e-3) / 1e9
+    l2_r["frac_of_hot_stream"] = l2_r["kernel_l2_GBps"] / l2_r["hot"]["GBps"]
     lib_r = measure_library_gemm(p, args.steps, args.warmup)
     lib_r["sparse_speedup_over_library_dense"] = lib_r["ms"] / main_r["ms"]
 
@@ -253,6 +291,7 @@ def main():
         "identity_perm": {"ms": ident_r["ms"], "shuffled_over_identity": main_r["ms"] / ident_r["ms"]},
         "conv2d_config4": conv_r,
         "bf16_operands": {"ms": bf16_r["ms"], "tflops": bf16_r["tflops"]},
+        "l2_stream_probe": l2_r,
         "library_dense_gemm": lib_r,
         "cpu_baseline": cpu,
         "context": PAPER_CONTEXT,

@@ -14,6 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libshflbw.so")
+PROBE_LIB = os.path.join(HERE, "libshflbw_probe.so")
 SOURCES = ["compress.cpp", "api_device.hip", "launch_gather_f16.hip", "launch_gather_bf16.hip"]
 # packed fp32 instructions are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -44,6 +45,11 @@ def build(verbose=True, extra=()):
     tmp = LIB + ".tmp.%d" % os.getpid()
     subprocess.check_call([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs)
     os.replace(tmp, LIB)
+    # the benchmark's L2 streaming probe: a library of its own, not part of the product
+    tmp = PROBE_LIB + ".tmp.%d" % os.getpid()
+    subprocess.check_call([hipcc, "-x", "hip", os.path.join(CSRC, "l2_probe.hip"), "-shared", "-o", tmp]
+                          + FLAGS + list(extra), stderr=subprocess.DEVNULL)
+    os.replace(tmp, PROBE_LIB)
     if verbose:
         print("built %s in %.1f s" % (LIB, time.time() - t0))
     return LIB

@@ -1,0 +1,105 @@
+// L2-to-LDS streaming probe (measurement aid for the benchmark, not part of
+// the product path).  It moves data the way the slab kernel's loader
+// wavefronts do - direct global-to-LDS loads of 16 bytes per lane, 64-row x
+// 256-byte chunks of a row-major matrix, a fixed number of chunks in flight -
+// and nothing else, so its rate is the ceiling for that kernel's activation
+// stream:
+//   mode 0  256 workgroups re-read 64 slabs `passes` times, four sharers per
+//           slab, the 8 slabs of an XCD (2 MB at K = 1024) staying in its L2
+//           (what the L2s can deliver into the CUs at best);
+//   mode 1  the slab kernel's grid and sharing pattern (workgroups that share
+//           a slab run side by side on one XCD), one pass, operands cold.
+// Built as its own small library (libshflbw_probe.so); only bench.py loads it.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace {
+
+constexpr int PROBE_KC = 64;        // rows per chunk
+constexpr int PROBE_STAGES = 8;     // LDS ring
+constexpr int PROBE_LEAD = 4;       // chunks in flight
+constexpr int PROBE_LOADERS = 4;    // wavefronts per workgroup
+
+__device__ __forceinline__ void dma16(const void* g, unsigned lds_off)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_off), "v"(g) : "memory");
+}
+
+__global__ __launch_bounds__(64 * PROBE_LOADERS) void l2_stream_kernel(
+    const uint16_t* X, long ldx, int K, int n_tiles, int gblocks, int passes, float* sink)
+{
+    __shared__ __attribute__((aligned(1024))) char smem[PROBE_STAGES * PROBE_KC * 256];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+    const int lrow = lane >> 4, lpos = lane & 15;
+    const int C = K / PROBE_KC;                      // K is a multiple of 64 (checked on the host)
+    const int wg = blockIdx.x, xcd = wg & 7, wslot = wg >> 3;
+    const int nt = (wslot / gblocks) * 8 + xcd;
+    if (nt >= n_tiles) return;
+    const uint16_t* Xt = X + (long)nt * 128;
+    const int total = C * passes;
+    auto issue = [&](int cg) __attribute__((always_inline)) {
+        const int c = cg % C;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int piece = wave * 4 + i;
+            const int row = c * PROBE_KC + 4 * piece + lrow;
+            dma16(Xt + (long)row * ldx + lpos * 8,
+                  base + (cg % PROBE_STAGES) * (PROBE_KC * 256) + piece * 1024);
+        }
+    };
+#pragma unroll
+    for (int cg = 0; cg < PROBE_LEAD; ++cg)
+        if (cg < total) issue(cg);
+    for (int cg = 0; cg < total; ++cg) {
+        int younger = total - 1 - cg;
+        younger = younger < PROBE_LEAD - 1 ? younger : PROBE_LEAD - 1;
+        switch (younger) {
+            case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+            case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+            case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+            default: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+        }
+        static_assert(PROBE_LEAD <= 4, "extend the switch above");
+        if (cg + PROBE_LEAD < total) issue(cg + PROBE_LEAD);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0 && *(volatile float*)(smem + 4 * (wg & 63)) == 12345.678f) sink[0] = 1.f;
+}
+
+}  // namespace
+
+extern "C" {
+
+/* Streams K x 128-column slabs of the row-major 16-bit matrix X (K x N, leading dimension
+ * ldx, device memory) into LDS.  mode 0: 256 workgroups over the first 64 slabs, `passes` times.
+ * mode 1: the slab kernel's grid for `gblocks` sharers per slab, one pass.  Enqueues on
+ * `stream`; returns the bytes moved into LDS, or a negative value on bad arguments.
+ * K must be a multiple of 64, N a multiple of 128 and at least 8192. */
+long long shflbw_probe_l2_stream(const void* X, long long ldx, int K, long long N, int mode,
+                                 int gblocks, int passes, void* sink, void* stream)
+{
+    if (!X || !sink || K <= 0 || K % PROBE_KC || N < 8192 || N % 128 || ldx < N || passes < 1 ||
+        gblocks < 1)
+        return -1;
+    const int n_tiles = (int)(N / 128);
+    int wgs, gb;
+    int tiles = n_tiles;
+    if (mode == 0) { gb = 4; tiles = 64; wgs = 256; }
+    else { gb = gblocks; passes = 1; wgs = (n_tiles + 7) / 8 * 8 * gb; }
+    if (tiles > n_tiles) return -1;
+    hipLaunchKernelGGL(l2_stream_kernel, dim3((unsigned)wgs), dim3(64 * PROBE_LOADERS), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(X), (long)ldx, K,
+                       tiles, gb, passes, static_cast<float*>(sink));
+    if (hipGetLastError() != hipSuccess) return -2;
+    long long active = 0;   // workgroups whose column tile exists
+    for (int wg = 0; wg < wgs; ++wg)
+        if (((wg >> 3) / gb) * 8 + (wg & 7) < tiles) ++active;
+    return active * (long long)K * 256 * passes;
+}
+
+}  // extern "C"

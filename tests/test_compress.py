@@ -168,3 +168,12 @@ def test_bfloat16_weights_round_trip_bitwise():
     B = binding.compress(W, None, p.perm, 32)
     cols = B.group_columns(0)
     assert 5 not in cols and 6 not in cols
+
+
+def test_probe_library_loads_and_exports_its_entry_point():
+    """The benchmark's L2 streaming probe is a library of its own (no compute call here)."""
+    import ctypes
+    import os
+    path = os.path.join(os.path.dirname(binding.__file__), "libshflbw_probe.so")
+    lib = ctypes.CDLL(path)
+    assert hasattr(lib, "shflbw_probe_l2_stream")
