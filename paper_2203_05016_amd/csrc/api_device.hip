@@ -94,6 +94,7 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
                int ph, int pw, int Ho, int Wo, bool chwn, ConvArgs& a, size_t& lds_bytes)
 {
     if (A->V != 32 && A->V != 64) return false;
+    if (A->K >= (1 << 20) || (long)R * S >= (1 << 20)) return false;   // exact division by multiplication
     const int gblocks = (A->G + CONV_GW - 1) / CONV_GW;
     const size_t list_bytes = CONV_LIST_BYTES;   // per-wavefront lists of LDS offsets
     const size_t lds_cap = 160 * 1024 - 512;
@@ -159,6 +160,9 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     a.rows_in = (th - 1) * sh + R; a.cols_in = (tw - 1) * sw + S;
     a.b_fast = chwn ? 1 : 0;
     a.gblocks = gblocks;
+    auto magic = [](int d) { return (((unsigned long long)1 << 40) + d - 1) / (unsigned long long)d; };
+    a.m_RS = magic(R * S); a.m_S = magic(S); a.m_tb = magic(tb); a.m_cols_in = magic(a.cols_in);
+    a.m_tw = magic(tw); a.m_th = magic(th);
     size_t in_bytes = (staged_elems(th, tw, tb) * 2 + 15) / 16 * 16;
     const size_t scratch = (size_t)CONV_GW * CONV_SCRATCH;
     if (in_bytes < scratch) in_bytes = scratch;
@@ -171,9 +175,17 @@ template <int V, int NT, typename OutT, bool BF>
 int launch_conv_nt(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStream_t stream)
 {
     a.A = view_of(A);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shflbw_conv_kernel<V, NT, OutT, BF>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    // the attribute is raised once per kernel and device, to the most any box can ask for
+    static thread_local int raised_on = -1;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (raised_on != dev) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shflbw_conv_kernel<V, NT, OutT, BF>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+        raised_on = dev;
+    }
     const long wgs = (long)a.nb * a.ny * a.nx * a.gblocks;
     hipLaunchKernelGGL((shflbw_conv_kernel<V, NT, OutT, BF>), dim3((unsigned)wgs), dim3(64 * CONV_GW), lds_bytes,
                        stream, a);

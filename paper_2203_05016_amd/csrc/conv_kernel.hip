@@ -57,7 +57,15 @@ struct ConvArgs {
     int b_fast;               // 1: batch runs fastest in the local index (CHWN)
     int gblocks;              // blocks of CONV_GW groups
     int in_bytes;             // LDS bytes reserved for the staged input (and the scratch)
+    // ceil(2^40 / d) for the divisors the kernel needs: x / d == (x * m) >> 40 for x, d < 2^20
+    unsigned long long m_RS, m_S, m_tb, m_cols_in, m_tw, m_th;
 };
+
+// Exact quotient by a divisor known on the host (both below 2^20).
+__device__ __forceinline__ int conv_div(int x, unsigned long long m)
+{
+    return (int)(((unsigned long long)(unsigned)x * m) >> 40);
+}
 
 // NT: 32-position instruction tiles per box (1, 2 or 4; a box holds at most 32*NT positions).
 template <int V, int NT, typename OutT, bool BF>
@@ -107,8 +115,8 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
             const int k = cols[i];
             int off = zero_off;
             if (k >= 0) {
-                const int c = k / RS, rs = k - c * RS;
-                const int r = rs / a.S, sx = rs - r * a.S;
+                const int c = conv_div(k, a.m_RS), rs = k - c * RS;
+                const int r = conv_div(rs, a.m_S), sx = rs - r * a.S;
                 off = c * plane + (r * a.cols_in + sx) * a.tb;
             }
             klist[i * 64 + lane] = (uint16_t)off;
@@ -116,12 +124,22 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     };
     int cols0[BULK_LOADS];
     load_cols(0, cols0);   // in flight while the input box is staged
+    // so are the weight operands of the first CONV_PD steps
+    const half8* valp = a.A.values + (long)sbeg * RB * 64 + lane;
+    const int last = nsteps - 1;
+    half8 w[CONV_PD][RB];
+#pragma unroll
+    for (int u = 0; u < CONV_PD; ++u) {
+        const int sn = u < nsteps ? u : last;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            w[u][rb] = nsteps > 0 ? valp[((long)sn * RB + rb) * 64] : half8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
 
     // ---- stage the input box: element (c, iy, ix, bb) at xin[c*plane + (iy*cols_in + ix)*tb + bb]
     for (int p = lane; p < plane; p += 64) {
-        const int bb = p % a.tb;
-        const int q = p / a.tb;
-        const int ix = q % a.cols_in, iy = q / a.cols_in;
+        const int q = conv_div(p, a.m_tb), bb = p - q * a.tb;
+        const int iy = conv_div(q, a.m_cols_in), ix = q - iy * a.cols_in;
         const int yy = iy0 + iy, xx = ix0 + ix, b = b0 + bb;
         const bool inside = yy >= 0 && yy < a.H && xx >= 0 && xx < a.W && b < a.B;
         const _Float16* src = a.in + (inside ? b * a.isB + yy * a.isH + xx * a.isW : 0);
@@ -153,8 +171,13 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     for (int t = 0; t < NT; ++t) {
         const int n = 32 * t + (lane & 31);
         int bb, yy, xx;
-        if (a.b_fast) { bb = n % a.tb; const int q = n / a.tb; xx = q % a.tw; yy = q / a.tw; }
-        else { xx = n % a.tw; const int q = n / a.tw; yy = q % a.th; bb = q / a.th; }
+        if (a.b_fast) {
+            const int q = conv_div(n, a.m_tb);
+            bb = n - q * a.tb; yy = conv_div(q, a.m_tw); xx = q - yy * a.tw;
+        } else {
+            const int q = conv_div(n, a.m_tw);
+            xx = n - q * a.tw; bb = conv_div(q, a.m_th); yy = q - bb * a.th;
+        }
         const int b = b0 + bb, y = y0 + yy, x = x0 + xx;
         live[t] = n < npos && b < a.B && y < a.Ho && x < a.Wo;
         noff[t] = live[t] ? (yy * a.sh * a.cols_in + xx * a.sw) * a.tb + bb : 0;
@@ -171,18 +194,9 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
 
     if (nsteps > 0) {
         const int khalf = lane >> 5;
-        const half8* valp = a.A.values + (long)sbeg * RB * 64 + lane;
-        const int last = nsteps - 1;
         typedef unsigned short ushort8 __attribute__((ext_vector_type(8)));
         const ushort8* kl = reinterpret_cast<const ushort8*>(klist) + khalf;   // 8 slots of this lane's half
 
-        half8 w[CONV_PD][RB];
-#pragma unroll
-        for (int u = 0; u < CONV_PD; ++u) {
-            const int sn = u < nsteps ? u : last;
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) w[u][rb] = valp[((long)sn * RB + rb) * 64];
-        }
         // StitchTile of one step: 8 reduction indices x up to NT positions per lane
         auto gather = [&](int s, half8 (&x)[NT]) __attribute__((always_inline)) {
             const ushort8 ko = kl[(s & (CONV_BULK - 1)) * 2];
