@@ -118,3 +118,26 @@ def scatter_rows(tiles, row_indices):
     out = np.empty_like(tiles)
     out[np.asarray(row_indices)] = tiles
     return out
+
+
+def layernorm_transpose(x, gamma=None, beta=None, eps=1e-5, normalize=True):
+    """The layout step of Section 4.3's discussion: activations that a
+    LayerNorm produces feature-innermost, ``x`` of shape (N tokens, K
+    features), are handed to the sparse kernels batch-innermost, i.e. as the
+    (K, N) matrix.  With ``normalize`` the LayerNorm itself is applied on the
+    way (per token: subtract the mean over the K features, divide by
+    sqrt(biased variance + eps), times gamma plus beta); without it the result
+    is the plain transpose.  float64 throughout.  Returns (Y, S) with S the
+    magnitude the tolerance is stated against: |gamma| |x_hat| + |beta|."""
+    xd = np.asarray(x, dtype=np.float64)
+    N, K = xd.shape
+    g = np.ones(K) if gamma is None else np.asarray(gamma, dtype=np.float64)
+    b = np.zeros(K) if beta is None else np.asarray(beta, dtype=np.float64)
+    if not normalize:
+        return xd.T.copy(), np.abs(xd.T)
+    mean = xd.mean(axis=1, keepdims=True)
+    var = ((xd - mean) ** 2).mean(axis=1, keepdims=True)
+    xhat = (xd - mean) / np.sqrt(var + eps)
+    y = xhat * g[None, :] + b[None, :]
+    s = np.abs(xhat) * np.abs(g)[None, :] + np.abs(b)[None, :]
+    return y.T.copy(), s.T.copy()

@@ -344,3 +344,38 @@ def test_bfloat16_rounding_of_the_generator_matches_library():
     bits = synth.float32_to_bfloat16_bits(a)
     want = torch.from_numpy(a).to(torch.bfloat16)
     assert np.array_equal(bits.view(np.int16), want.view(torch.int16).numpy())
+
+
+# ----------------------------------------------------------------- LayerNorm-side transposition
+def test_layernorm_transpose_matches_library_layer_norm():
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal((37, 96)).astype(np.float16)
+    gamma = rng.standard_normal(96).astype(np.float16)
+    beta = rng.standard_normal(96).astype(np.float16)
+    got, _ = definition.layernorm_transpose(x, gamma, beta, eps=1e-5)
+    want = torch.nn.functional.layer_norm(torch.from_numpy(x.astype(np.float64)), (96,),
+                                          torch.from_numpy(gamma.astype(np.float64)),
+                                          torch.from_numpy(beta.astype(np.float64)), 1e-5).numpy().T
+    assert got.shape == (96, 37) and np.allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_layernorm_transpose_closed_forms_and_invariants():
+    # a constant row has zero variance: the output is beta whatever the constant
+    x = np.full((3, 8), 2.5)
+    beta = np.arange(8.0)
+    y, _ = definition.layernorm_transpose(x, np.ones(8), beta)
+    assert np.allclose(y, np.tile(beta[:, None], (1, 3)))
+    # two features {a, b}: x_hat = -+ 1/sqrt(1 + 4 eps/(a-b)^2)
+    y, _ = definition.layernorm_transpose(np.array([[1.0, 3.0]]), eps=0.25)
+    assert np.allclose(y[:, 0], [-1 / np.sqrt(1.25), 1 / np.sqrt(1.25)])
+    # shifting a token by a constant changes nothing; scaling by c > 0 only through eps
+    rng = np.random.default_rng(42)
+    x = rng.standard_normal((5, 64))
+    y0, _ = definition.layernorm_transpose(x, eps=0.0)
+    y1, _ = definition.layernorm_transpose(x * 3.0 + 7.0, eps=0.0)
+    assert np.allclose(y0, y1, atol=1e-12)
+    # per token: zero mean and unit variance over the features when eps = 0, gamma = 1, beta = 0
+    assert np.allclose(y0.mean(axis=0), 0, atol=1e-12) and np.allclose(y0.var(axis=0), 1, atol=1e-12)
+    # without normalisation it is the transpose, element for element
+    t, _ = definition.layernorm_transpose(x, normalize=False)
+    assert np.array_equal(t, x.T)
