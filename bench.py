@@ -151,6 +151,29 @@ def measure_library_gemm(p, steps, warmup):
     return dict(ms=ms, dense_tflops=2.0 * p.M * p.K * p.N / (ms * 1e-3) / 1e12)
 
 
+def measure_layernorm_transpose(p, steps, warmup):
+    """The LayerNorm-side transposition that hands token-major activations (N x K) to the
+    headline product as X (K x N); HBM-bound: 2*N*K bytes read, 2*N*K written."""
+    import torch
+    from paper_2203_05016_amd import binding
+    rot = rotation_for(p)
+    rng = np.random.Generator(np.random.PCG64(12))
+    xs = [torch.from_numpy(rng.standard_normal((p.N, p.K), dtype=np.float32).astype(np.float16)).to("cuda:0")
+          for _ in range(rot)]
+    outs = [torch.empty((p.K, p.N), dtype=torch.float16, device="cuda:0") for _ in range(rot)]
+    gamma = torch.ones(p.K, dtype=torch.float16, device="cuda:0")
+    beta = torch.zeros(p.K, dtype=torch.float16, device="cuda:0")
+    state = {"i": 0}
+
+    def fn():
+        j = state["i"] % rot
+        binding.layernorm_transpose(xs[j], gamma, beta, 1e-5, out=outs[j])
+        state["i"] += 1
+    ms = time_steps(fn, steps, warmup)
+    nbytes = 4.0 * p.N * p.K
+    return dict(ms=ms, bytes=nbytes, GBps=nbytes / (ms * 1e-3) / 1e9, hbm_frac=nbytes / (ms * 1e-3) / HBM_PEAK)
+
+
 def measure_l2_stream(p):
     """The probe library's two streaming runs on the headline's X: the rate at which the
     L2s can feed LDS with this access pattern when nothing else runs (hot), and with the
@@ -258,6 +281,8 @@ def main():
     conv_r["dense_ms"] = conv_dense["ms"]
     bf16_r = measure_spmm(synth.config(1, fmt="bf16"), args.steps, args.warmup, cold=True,
                           tile_n=args.tile_n, kernel=args.kernel)
+    ln_r = measure_layernorm_transpose(p, args.steps, args.warmup)
+    ln_r["fraction_of_headline_time"] = ln_r["ms"] / main_r["ms"]
     l2_r = measure_l2_stream(p)
     # bytes the headline kernel pulls from the L2s into its CUs per launch (TCP_TCC_READ_REQ x 128 B,
     # profiles/slab_kernel_ffn_config2_pmc.md) over its launch time, against the probe's rates
@@ -291,6 +316,7 @@ def main():
         "identity_perm": {"ms": ident_r["ms"], "shuffled_over_identity": main_r["ms"] / ident_r["ms"]},
         "conv2d_config4": conv_r,
         "bf16_operands": {"ms": bf16_r["ms"], "tflops": bf16_r["tflops"]},
+        "layernorm_transpose": ln_r,
         "l2_stream_probe": l2_r,
         "library_dense_gemm": lib_r,
         "cpu_baseline": cpu,

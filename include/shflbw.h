@@ -155,6 +155,26 @@ int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out,
                   int stride_h, int stride_w, int pad_h, int pad_w,
                   shflbw_layout layout, shflbw_dtype ydtype, void* stream);
 
+/*
+ * LayerNorm-side transposition (Section 4.3, discussion of the activation
+ * layout: models whose LayerNorm leaves the features contiguous hand their
+ * activations to these kernels through a transposition folded into that
+ * LayerNorm).
+ *  x      device, N x K of dtype (SHFLBW_F16 or SHFLBW_BF16): N tokens, K features
+ *         innermost, leading dimension ldx >= K.
+ *  gamma, beta  device, K values of dtype, or NULL (1 and 0).
+ *  normalize    non-zero: per token, subtract the mean over the K features, divide by
+ *         sqrt(biased variance + eps), multiply by gamma, add beta (statistics in
+ *         fp32).  Zero: copy only (gamma, beta, eps ignored).
+ *  out    device, K x N of dtype, leading dimension ldo >= N: the matrix shflbw_spmm
+ *         takes as X.  Must not overlap x.
+ * K, N, ldx, ldo must be multiples of 8 and all bases 16-byte aligned
+ * (SHFLBW_ERR_BAD_SHAPE otherwise).  N == 0 is a no-op.  Enqueues on `stream` only.
+ */
+int shflbw_layernorm_transpose(const void* x, int64_t ldx, const void* gamma, const void* beta,
+                               float eps, int normalize, void* out, int64_t ldo, int64_t N,
+                               int K, shflbw_dtype dtype, void* stream);
+
 const char* shflbw_status_string(int status);
 const char* shflbw_last_error(void); /* thread-local, never NULL */
 

@@ -22,8 +22,8 @@ _lib = None
 EXPORTS = [
     "shflbw_compress", "shflbw_destroy", "shflbw_info", "shflbw_row_indices",
     "shflbw_group_columns", "shflbw_decompress", "shflbw_device_bytes", "shflbw_bind_device",
-    "shflbw_set_tuning", "shflbw_spmm", "shflbw_conv2d", "shflbw_status_string",
-    "shflbw_last_error",
+    "shflbw_set_tuning", "shflbw_spmm", "shflbw_conv2d", "shflbw_layernorm_transpose",
+    "shflbw_status_string", "shflbw_last_error",
 ]
 
 
@@ -64,6 +64,9 @@ def lib():
         L.shflbw_spmm.argtypes = [vp, vp, i64, vp, i64, i64, i32, vp]
         L.shflbw_conv2d.restype = i32
         L.shflbw_conv2d.argtypes = [vp, vp, vp] + [i32] * 10 + [i32, i32, vp]
+        L.shflbw_layernorm_transpose.restype = i32
+        L.shflbw_layernorm_transpose.argtypes = [vp, i64, vp, vp, ctypes.c_float, i32, vp, i64, i64,
+                                                 i32, i32, vp]
         L.shflbw_status_string.restype = ctypes.c_char_p
         L.shflbw_status_string.argtypes = [i32]
         L.shflbw_last_error.restype = ctypes.c_char_p
@@ -229,3 +232,27 @@ def compress(W, mask, perm, V, K=None):
     _check(lib().shflbw_compress(_host_ptr(W), ldw, _host_ptr(m), _host_ptr(p), M, K, V,
                                  BF16 if bf16 else F16, ctypes.byref(h)))
     return Matrix(h, bf16)
+
+
+def layernorm_transpose(x, gamma=None, beta=None, eps=1e-5, normalize=True, out=None, stream=None):
+    """shflbw_layernorm_transpose on device tensors: x (N tokens, K features)
+    float16 or bfloat16 with unit feature stride; returns the (K, N) matrix
+    shflbw_spmm takes as X."""
+    import torch
+    if x.dtype not in (torch.float16, torch.bfloat16) or x.dim() != 2 or x.stride(1) != 1:
+        raise TypeError("x must be a 2-D float16 or bfloat16 tensor with unit feature stride")
+    N, K = x.shape
+    for t in (gamma, beta):
+        if t is not None and (t.dtype != x.dtype or t.shape != (K,) or not t.is_contiguous()):
+            raise TypeError("gamma and beta must be contiguous (K,) tensors of x's dtype")
+    if out is None:
+        out = torch.empty((K, N), dtype=x.dtype, device=x.device)
+    if out.dtype != x.dtype or out.shape != (K, N) or out.stride(1) != 1:
+        raise TypeError("out must be a (K, N) tensor of x's dtype with unit token stride")
+    ptr = lambda t: ctypes.c_void_p(None if t is None else t.data_ptr())
+    _check(lib().shflbw_layernorm_transpose(ptr(x), x.stride(0) if N > 1 else K, ptr(gamma), ptr(beta),
+                                            float(eps), 1 if normalize else 0, ptr(out),
+                                            out.stride(0) if K > 1 else N, N, K,
+                                            BF16 if x.dtype == torch.bfloat16 else F16,
+                                            _stream_ptr(stream)))
+    return out
