@@ -17,6 +17,12 @@
 // workgroup's range are loaded up to four blocks ahead (16 bytes per lane),
 // normalised in fp32, written transposed into an LDS tile and stored as 64
 // rows of 128 bytes.  It is bound by HBM: 2*N*K bytes read and 2*N*K written.
+//
+// When a block of 64 (or 32) tokens with all its features fits the LDS, a
+// second kernel keeps it there instead: every activation is read from HBM
+// once, the statistics come from the same loads, and the transposed rows are
+// gathered from LDS columns (row pitch chosen so that the 8 token rows a
+// lane reads fall into different banks).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -203,6 +209,117 @@ __global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_kernel(LnAr
     }
 }
 
+// ---------------------------------------------------------------- LDS-resident variant
+// TOK tokens x K features (pitch P halves, P/2 = 1 mod 64) + statistics + gamma/beta in fp32.
+template <bool BF, int TOK>
+__global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_resident_kernel(LnArgs a, int P)
+{
+    extern __shared__ __attribute__((aligned(16))) char ln_smem[];
+    uint16_t* xs = reinterpret_cast<uint16_t*>(ln_smem);                       // [TOK][P]
+    float* st_mean = reinterpret_cast<float*>(ln_smem + (size_t)TOK * P * 2);   // [TOK]
+    float* st_rstd = st_mean + TOK;                                             // [TOK]
+    float* gam = st_rstd + TOK;                                                 // [K]
+    float* bet = gam + a.K;                                                     // [K]
+    constexpr int TPW = TOK / LN_WAVES;   // tokens per wavefront
+    constexpr int CH = TOK / 8;           // 16-byte token chunks per output row
+    constexpr int FW = 64 / CH;           // features one wavefront stores per pass
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const long n0 = (long)blockIdx.x * TOK;
+    const int K = a.K;
+
+    for (int k = tid; k < K; k += 64 * LN_WAVES) {
+        gam[k] = (a.normalize && a.gamma) ? ln_widen<BF>(a.gamma[k]) : 1.f;
+        bet[k] = (a.normalize && a.beta) ? ln_widen<BF>(a.beta[k]) : 0.f;
+    }
+
+    // ---- load the block once: LDS copy and, from the same registers, the statistics
+    float s1[TPW], s2[TPW], pivot[TPW];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) { s1[t] = 0.f; s2[t] = 0.f; pivot[t] = 0.f; }
+    for (int kc0 = 0; kc0 < K; kc0 += 2 * 64 * 8) {
+        ln_ushort8 v[TPW][2];
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            const long n = n0 + wave * TPW + t;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int kc = kc0 + h * 512 + lane * 8;
+                v[t][h] = ln_ushort8{0, 0, 0, 0, 0, 0, 0, 0};
+                if (n < a.N && kc < K) v[t][h] = *reinterpret_cast<const ln_ushort8*>(a.x + n * a.ldx + kc);
+            }
+        }
+        if (kc0 == 0) {
+#pragma unroll
+            for (int t = 0; t < TPW; ++t)
+                pivot[t] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
+                    __builtin_bit_cast(int, ln_widen<BF>(v[t][0][0]))));
+        }
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int kc = kc0 + h * 512 + lane * 8;
+                if (kc < K) {
+                    unsigned* dst = reinterpret_cast<unsigned*>(xs + (wave * TPW + t) * P + kc);   // 4-byte aligned
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        dst[e] = (unsigned)v[t][h][2 * e] | ((unsigned)v[t][h][2 * e + 1] << 16);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float d = ln_widen<BF>(v[t][h][e]) - pivot[t];
+                        s1[t] += d;
+                        s2[t] += d * d;
+                    }
+                }
+            }
+        }
+    }
+    if (a.normalize) {
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                s1[t] += __shfl_xor(s1[t], off, 64);
+                s2[t] += __shfl_xor(s2[t], off, 64);
+            }
+        }
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            const float m = s1[t] / (float)K;
+            float var = s2[t] / (float)K - m * m;
+            var = var > 0.f ? var : 0.f;
+            st_mean[wave * TPW + t] = a.normalize ? pivot[t] + m : 0.f;
+            st_rstd[wave * TPW + t] = a.normalize ? 1.0f / __builtin_sqrtf(var + a.eps) : 1.f;
+        }
+    }
+    __syncthreads();
+
+    // ---- transposed rows: a wavefront stores FW feature rows x TOK tokens per pass;
+    // lane -> feature lane/CH of the pass, tokens (lane%CH)*8 .. +7
+    const int kk = lane / CH, tchunk = lane % CH;
+    float mean[8], rstd[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { mean[e] = st_mean[tchunk * 8 + e]; rstd[e] = st_rstd[tchunk * 8 + e]; }
+    const long n = n0 + tchunk * 8;
+    for (int kb = wave * FW; kb < K; kb += LN_WAVES * FW) {
+        const int k = kb + kk;
+        if (k < K && n < a.N) {
+            const float g = gam[k], b = bet[k];
+            ln_ushort8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint16_t raw = xs[(tchunk * 8 + e) * P + k];
+                o[e] = a.normalize ? ln_narrow<BF>((ln_widen<BF>(raw) - mean[e]) * rstd[e] * g + b) : raw;
+            }
+            *reinterpret_cast<ln_ushort8*>(a.out + (long)k * a.ldo + n) = o;
+        }
+    }
+}
+
 }  // namespace
 }  // namespace shflbw
 
@@ -233,13 +350,49 @@ extern "C" int shflbw_layernorm_transpose(const void* x, int64_t ldx, const void
     a.out = static_cast<uint16_t*>(out);
     a.ldx = (long)ldx; a.ldo = (long)ldo; a.N = (long)N; a.K = K; a.eps = eps;
     a.normalize = normalize ? 1 : 0;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // LDS-resident variant when a block of tokens with all its features fits: 64 tokens per
+    // workgroup, or 32 when that fills the chip better or is all that fits
+    auto resident_bytes = [&](int tok, int& pitch) {
+        int pad = 2;
+        while (((K + pad) / 2) % 64 != 1) pad += 2;     // 8 rows apart -> 8 banks apart
+        pitch = K + pad;
+        return (size_t)tok * pitch * 2 + 2 * (size_t)tok * 4 + 2 * (size_t)K * 4;
+    };
+    const size_t lds_cap = 160 * 1024 - 256;
+    int pitch = 0;
+    int tok = 0;
+    if (resident_bytes(64, pitch) <= lds_cap && (N + 63) / 64 >= 256) tok = 64;
+    else if (resident_bytes(32, pitch) <= lds_cap) tok = 32;
+    if (tok) {
+        const size_t bytes = resident_bytes(tok, pitch);
+        const int64_t rwgs = (N + tok - 1) / tok;
+        if (rwgs > 0x7fffffffLL) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
+        const void* fn = dtype == SHFLBW_BF16
+            ? (tok == 64 ? (const void*)&layernorm_transpose_resident_kernel<true, 64>
+                         : (const void*)&layernorm_transpose_resident_kernel<true, 32>)
+            : (tok == 64 ? (const void*)&layernorm_transpose_resident_kernel<false, 64>
+                         : (const void*)&layernorm_transpose_resident_kernel<false, 32>);
+        hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (ea != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(ea));
+        const dim3 grid((unsigned)rwgs), block(64 * LN_WAVES);
+        if (dtype == SHFLBW_BF16) {
+            if (tok == 64) hipLaunchKernelGGL((layernorm_transpose_resident_kernel<true, 64>), grid, block, bytes, st, a, pitch);
+            else hipLaunchKernelGGL((layernorm_transpose_resident_kernel<true, 32>), grid, block, bytes, st, a, pitch);
+        } else {
+            if (tok == 64) hipLaunchKernelGGL((layernorm_transpose_resident_kernel<false, 64>), grid, block, bytes, st, a, pitch);
+            else hipLaunchKernelGGL((layernorm_transpose_resident_kernel<false, 32>), grid, block, bytes, st, a, pitch);
+        }
+        hipError_t el = hipGetLastError();
+        if (el != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(el));
+        return SHFLBW_OK;
+    }
     // split the features over grid.y until there are about two workgroups per CU
     const int nblocks = (K + LN_FB - 1) / LN_FB;
     int split = 1;
     while (wgs * split < 512 && split * 2 <= nblocks && split < 16) split *= 2;
     a.blocks_per_wg = (nblocks + split - 1) / split;
     const unsigned gy = (unsigned)((nblocks + a.blocks_per_wg - 1) / a.blocks_per_wg);
-    hipStream_t st = static_cast<hipStream_t>(stream);
     if (dtype == SHFLBW_BF16)
         hipLaunchKernelGGL(layernorm_transpose_kernel<true>, dim3((unsigned)wgs, gy), dim3(64 * LN_WAVES), 0, st, a);
     else
