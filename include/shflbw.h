@@ -88,6 +88,26 @@ typedef enum {
 int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* perm,
                     int M, int K, int V, shflbw_dtype wdtype, shflbw_matrix** out);
 
+/*
+ * Pattern search (Section 5), host only: from the weights alone, choose the row shuffle
+ * and the kept V x 1 vectors; the results feed shflbw_compress.  Importance = |w|;
+ * unstructured pruning to the non-zero ratio beta gives a binary mask; K-Means with
+ * clusters of the fixed size V on the rows of that mask groups the rows; vector-wise
+ * pruning to the non-zero ratio alpha on the shuffled matrix; the shuffle is undone.
+ *  W      host, M x K binary16 (SHFLBW_F16 only), finite, leading dimension ldw >= K.
+ *  alpha  target non-zero ratio in [0, 1]: every group keeps round(alpha*K) vectors.
+ *  beta   ratio of the unstructured step; negative = 2*alpha (capped at 1), the value
+ *         the paper recommends.
+ *  iterations  K-Means rounds at most (it stops when no row moves); 0 = no shuffle,
+ *         i.e. plain vector-wise pruning.
+ *  perm_out  M int32: perm_out[i] = original row of stored row i.
+ *  mask_out  M x K bytes (leading dimension K), original row order; conforms to the
+ *         pattern under perm_out.
+ * Deterministic: comparisons are exact and ties go to the lower index.
+ */
+int shflbw_pattern_search(const void* W, int ldw, int M, int K, int V, double alpha, double beta,
+                          int iterations, shflbw_dtype wdtype, int32_t* perm_out, uint8_t* mask_out);
+
 void shflbw_destroy(shflbw_matrix* A);
 
 /* Shape and sparsity of a packed matrix.  Any out pointer may be NULL.

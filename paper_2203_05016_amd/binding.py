@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libshflbw.so")
 _lib = None
 
 EXPORTS = [
-    "shflbw_compress", "shflbw_destroy", "shflbw_info", "shflbw_row_indices",
+    "shflbw_compress", "shflbw_pattern_search", "shflbw_destroy", "shflbw_info", "shflbw_row_indices",
     "shflbw_group_columns", "shflbw_decompress", "shflbw_device_bytes", "shflbw_bind_device",
     "shflbw_set_tuning", "shflbw_spmm", "shflbw_conv2d", "shflbw_layernorm_transpose",
     "shflbw_status_string", "shflbw_last_error",
@@ -64,6 +64,9 @@ def lib():
         L.shflbw_spmm.argtypes = [vp, vp, i64, vp, i64, i64, i32, vp]
         L.shflbw_conv2d.restype = i32
         L.shflbw_conv2d.argtypes = [vp, vp, vp] + [i32] * 10 + [i32, i32, vp]
+        L.shflbw_pattern_search.restype = i32
+        L.shflbw_pattern_search.argtypes = [vp, i32, i32, i32, i32, ctypes.c_double, ctypes.c_double,
+                                            i32, i32, vp, vp]
         L.shflbw_layernorm_transpose.restype = i32
         L.shflbw_layernorm_transpose.argtypes = [vp, i64, vp, vp, ctypes.c_float, i32, vp, i64, i64,
                                                  i32, i32, vp]
@@ -256,3 +259,18 @@ def layernorm_transpose(x, gamma=None, beta=None, eps=1e-5, normalize=True, out=
                                             BF16 if x.dtype == torch.bfloat16 else F16,
                                             _stream_ptr(stream)))
     return out
+
+
+def pattern_search(W, V, alpha, beta=None, iterations=10):
+    """shflbw_pattern_search on a numpy float16 matrix: returns (perm, mask)
+    ready for ``compress``.  beta None = the paper's 2*alpha."""
+    if W.dtype != np.float16 or W.ndim != 2:
+        raise TypeError("W must be a 2-D float16 array")
+    W = np.ascontiguousarray(W)
+    M, K = W.shape
+    perm = np.empty(M, dtype=np.int32)
+    mask = np.empty((M, K), dtype=np.uint8)
+    _check(lib().shflbw_pattern_search(_host_ptr(W), K, M, K, V, float(alpha),
+                                       -1.0 if beta is None else float(beta), int(iterations), F16,
+                                       _host_ptr(perm), _host_ptr(mask)))
+    return perm, mask

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libshflbw.so")
 PROBE_LIB = os.path.join(HERE, "libshflbw_probe.so")
-SOURCES = ["compress.cpp", "api_device.hip", "launch_gather_f16.hip", "launch_gather_bf16.hip",
+SOURCES = ["compress.cpp", "pattern_search.cpp", "api_device.hip", "launch_gather_f16.hip", "launch_gather_bf16.hip",
            "layernorm_transpose.hip"]
 # packed fp32 instructions are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

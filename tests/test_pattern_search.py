@@ -69,3 +69,46 @@ def test_kmeans_keeps_every_cluster_at_v_rows_and_is_deterministic():
     a = pattern_search.balanced_kmeans(B, 5, 6)
     assert np.array_equal(np.bincount(a, minlength=8), np.full(8, 5))
     assert np.array_equal(a, pattern_search.balanced_kmeans(B.copy(), 5, 6))
+
+
+# ----------------------------------------------------------------- the library against the oracle
+from paper_2203_05016_amd import binding
+
+
+@pytest.mark.parametrize("M,K,V,alpha,beta,its", [
+    (64, 96, 8, 0.25, None, 10), (48, 64, 4, 0.125, 0.125, 10), (128, 200, 32, 0.1, None, 4),
+    (32, 40, 16, 0.5, 1.0, 3), (12, 40, 1, 0.25, None, 3), (12, 40, 4, 0.25, None, 0),
+    (64, 72, 8, 0.0, None, 2), (64, 72, 8, 1.0, None, 2),
+])
+def test_library_search_equals_the_oracle_bit_for_bit(M, K, V, alpha, beta, its):
+    rng = np.random.Generator(np.random.PCG64(810 + M + K + V))
+    W = rng.standard_normal((M, K), dtype=np.float32).astype(np.float16)
+    W[rng.random((M, K)) < 0.05] = 0            # ties among zeros
+    W[0, :5] = W[1, :5]                          # ties among equal magnitudes
+    perm, mask = binding.pattern_search(W, V, alpha, beta, its)
+    perm_o, mask_o = pattern_search.search(W, V, alpha, beta, its)
+    assert np.array_equal(perm, perm_o)
+    assert np.array_equal(mask, mask_o)
+
+
+def test_library_search_on_planted_groups_and_into_compress():
+    W, truth, _ = _planted(96, 128, 8, 16, seed=811)
+    perm, mask = binding.pattern_search(W, 8, 16 / 128, 16 / 128, 10)
+    assert np.array_equal(mask, truth)
+    W2, truth2, _ = _planted(128, 160, 16, 24, seed=812)
+    perm2, mask2 = binding.pattern_search(W2, 16, 24 / 160, 24 / 160, 10)
+    assert np.array_equal(mask2, truth2)
+    A = binding.compress(W2, mask2, perm2, 16)
+    assert A.info()["nnz"] == int(truth2.sum())
+    assert np.array_equal(A.decompress().view(np.uint16), np.where(truth2 != 0, W2, np.float16(0)).view(np.uint16))
+
+
+def test_library_search_argument_checks():
+    W = np.zeros((8, 8), dtype=np.float16)
+    with pytest.raises(binding.ShflbwError):
+        binding.pattern_search(W, 3, 0.5)               # M % V != 0
+    with pytest.raises(binding.ShflbwError):
+        binding.pattern_search(W, 4, 1.5)               # alpha outside [0, 1]
+    W[0, 0] = np.inf
+    with pytest.raises(binding.ShflbwError):
+        binding.pattern_search(W, 4, 0.5)               # non-finite weight

@@ -219,3 +219,27 @@ def test_skinny_shape_is_routed_to_split_k_and_matches():
     Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
     for kernel in (0, 3, 1):
         assert_within_scaled_tolerance(run_spmm(p, kernel=kernel), Yr, S, what="skinny kernel %d" % kernel)
+
+
+def test_searched_pattern_end_to_end():
+    """Pattern search (Section 5) -> compress -> product, on weights whose large entries
+    follow hidden groups: the mask comes from the library's search, the product is
+    checked against the oracle with that mask."""
+    from paper_2203_05016_amd import binding
+    from gpu_util import to_device, to_host
+    announce("search -> compress -> spmm")
+    rng = np.random.Generator(np.random.PCG64(901))
+    M, K, N, V = 512, 640, 264, 32
+    W = (0.1 * rng.standard_normal((M, K), dtype=np.float32))
+    hidden = rng.permutation(M)
+    for g in range(M // V):
+        cols = rng.choice(K, 160, replace=False)
+        W[np.ix_(hidden[g * V:(g + 1) * V], cols)] += rng.standard_normal((V, 160), dtype=np.float32)
+    W = W.astype(np.float16)
+    X = rng.standard_normal((K, N), dtype=np.float32).astype(np.float16)
+    perm, mask = binding.pattern_search(W, V, 0.25, None, 8)
+    A = binding.compress(W, mask, perm, V).bind_device("cuda:0")
+    assert A.info()["nnz"] == M * 160
+    Y = to_host(A.spmm(to_device(X)))
+    Yr, S = c_oracle.spmm(W, mask, X)
+    assert_within_scaled_tolerance(Y, Yr, S, what="searched pattern")
