@@ -33,11 +33,13 @@
 // (column mod 384) of the lane's two transposed reads and the step's chunk.
 //
 // Algorithm 1's parts: BulkLoadMeta = each step's weight tile and table word
-// fetched into registers four steps ahead (the steps of a group come in
-// batches of four, so the four register sets are compile-time choices and
-// the compiler's own wait counts are exact);
+// fetched into registers four steps ahead (two for V = 64, whose two row
+// blocks of accumulators leave no room for more; the steps of a group come
+// in batches of four, so the register sets are compile-time choices and the
+// compiler's own wait counts are exact);
 // StitchTile = chunk streaming + gathered transposed reads; WarpMMA =
-// v_mfma_f32_32x32x16_f16 (16x16x32 for V = 16) with X^T as first operand;
+// v_mfma_f32_32x32x16_f16 (16x16x32 for V = 16; the bf16 forms with BF) with
+// X^T as first operand;
 // ReorderedWriteBack = accumulators through LDS, 128-byte row segments stored
 // to the rows named by row_indices.
 #pragma once
