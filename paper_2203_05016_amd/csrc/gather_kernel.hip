@@ -240,7 +240,7 @@ struct GatherShape {
 
 // SPLIT = false: the wavefronts of a workgroup own different column tiles of one
 // group.  SPLIT = true (few column tiles, the matrix-vector-like regime of
-// recurrent layers): they share one tile, each takes a contiguous quarter of
+// recurrent layers): they share one tile, each takes a contiguous share of
 // the group's k-steps, and the partial accumulators are summed through LDS
 // before the first wavefront writes the tile back.
 template <int V, int WN, int WAVES, int PD, typename OutT, class Geom, bool BF, bool SPLIT>

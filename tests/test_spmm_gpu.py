@@ -179,7 +179,7 @@ def test_config5_large_layer_sampled(variant):
 @pytest.mark.parametrize("V", [16, 32, 64, 128])
 @pytest.mark.parametrize("N", [1, 16, 64, 130])
 def test_split_k_gather_kernel(V, N):
-    """Four wavefronts share one column tile and a quarter of the k-steps each."""
+    """The wavefronts of a workgroup share one column tile and a share of the k-steps each."""
     announce("split-k", V, N)
     p = synth.make_spmm(3 * V, 777, N, V, 0.5, seed=601 + V + N)
     Y = run_spmm(p, kernel=3)
