@@ -130,7 +130,8 @@ struct GeomLinear {
                 vec_t v;
 #pragma unroll
                 for (int e = 0; e < CNT; ++e) v[e] = vals[e];
-                *reinterpret_cast<vec_t*>(p) = v;
+                // the output is not read again by this kernel: keep it from displacing X and W in the L2
+                __builtin_nontemporal_store(v, reinterpret_cast<vec_t*>(p));
             }
         } else {
 #pragma unroll

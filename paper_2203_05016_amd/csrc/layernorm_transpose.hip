@@ -315,7 +315,7 @@ __global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_resident_ke
                 const uint16_t raw = xs[(tchunk * 8 + e) * P + k];
                 o[e] = a.normalize ? ln_narrow<BF>((ln_widen<BF>(raw) - mean[e]) * rstd[e] * g + b) : raw;
             }
-            *reinterpret_cast<ln_ushort8*>(a.out + (long)k * a.ldo + n) = o;
+            __builtin_nontemporal_store(o, reinterpret_cast<ln_ushort8*>(a.out + (long)k * a.ldo + n));
         }
     }
 }

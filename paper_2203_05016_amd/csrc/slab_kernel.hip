@@ -347,7 +347,8 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
                 const int orig = out_row[rb][i];
                 const long n = n0 + pass * CW + echunk * OUT16;
                 if (n < a.N)
-                    *reinterpret_cast<vecw*>(static_cast<OutT*>(a.Y) + (long)orig * a.ldy + n) = v;
+                    // streaming store: Y must not displace the slab and the weights in the L2
+                    __builtin_nontemporal_store(v, reinterpret_cast<vecw*>(static_cast<OutT*>(a.Y) + (long)orig * a.ldy + n));
             }
             SHFLBW_WAVE_LDS_SYNC();
         }
