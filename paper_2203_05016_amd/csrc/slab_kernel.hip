@@ -146,6 +146,7 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
         // beyond N are redirected to valid addresses (their LDS bytes never
         // reach a stored result), so every load is issued and the count of
         // loads per chunk is exact.
+        __builtin_amdgcn_s_setprio(3);   // loaders issue ahead of the compute wavefronts of their SIMD
         const int lw = wave - GW;
         const int lrow = lane >> 4, lpos = lane & 15;
         const unsigned x_off = (unsigned)(size_t)(lds_char_ptr)smem;
