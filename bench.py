@@ -235,6 +235,8 @@ def main():
     ap.add_argument("--pmc", action="store_true",
                     help="counter-collection run: one 64 MiB device copy (calibration) and three "
                          "launches of the headline workload, nothing else")
+    ap.add_argument("--pmc-workload", default="headline", choices=["headline", "conv", "layernorm", "config5"],
+                    help="what --pmc launches three times after the calibration copy")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards over N "
@@ -254,11 +256,21 @@ def main():
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
-        c = Case(p, 3, tile_n=args.tile_n, kernel=args.kernel)
-        for _ in range(3):
-            c.step()
+        if args.pmc_workload == "conv":
+            measure_conv(synth.config(3), 3, 0, pairs=3)
+        elif args.pmc_workload == "layernorm":
+            measure_layernorm_transpose(p, 3, 0)
+        elif args.pmc_workload == "config5":
+            q = Case(synth.config(4, variant=1), 2)
+            for _ in range(3):
+                q.step()
+        else:
+            c = Case(p, 3, tile_n=args.tile_n, kernel=args.kernel)
+            for _ in range(3):
+                c.step()
         torch.cuda.synchronize()
-        print(json.dumps({"pmc_run": True, "copy_bytes_each_way": 64 << 20, "launches": 3}))
+        print(json.dumps({"pmc_run": True, "workload": args.pmc_workload,
+                          "copy_bytes_each_way": 64 << 20, "launches": 3}))
         return
     main_r = measure_spmm(p, args.steps, args.warmup, cold=True, tile_n=args.tile_n, kernel=args.kernel)
     if args.headline_only:
