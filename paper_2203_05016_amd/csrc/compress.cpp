@@ -165,9 +165,7 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
         const size_t steps = (size_t)A->step_ptr[G];
         A->col_idx.assign(steps * TK, -1);
         A->values.assign(steps * (size_t)V * TK, 0);
-        const int C = A->slab_chunks;
         if (A->slab_ok) A->step_iter.assign(steps, 0);
-        (void)C;
         for (int g = 0; g < G; ++g) {
             const int32_t* rows = &A->row_indices[(size_t)g * V];
             size_t step = (size_t)A->step_ptr[g];

@@ -34,7 +34,6 @@
 namespace shflbw {
 namespace {
 
-typedef _Float16 ln_half8 __attribute__((ext_vector_type(8)));
 typedef unsigned short ln_ushort8 __attribute__((ext_vector_type(8)));
 
 constexpr int LN_TOK = 64;       // tokens per workgroup

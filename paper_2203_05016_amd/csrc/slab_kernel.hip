@@ -63,13 +63,7 @@ static_assert(SLAB_IPL * (SLAB_LEAD - 1) < 16, "vmcnt immediates below use the l
 
 constexpr int SLAB_SPIN_LIMIT = 1 << 20;
 
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef __attribute__((address_space(3))) char* lds_char_ptr;
-typedef __attribute__((address_space(1))) const void* global_void_ptr;
-
-// s_waitcnt immediate for gfx9-family encodings: vmcnt (< 16) in bits [3:0],
-// expcnt [6:4] and lgkmcnt [11:8] left at "do not wait".
-#define SHFLBW_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
 
 // Direct global-to-LDS load issued from inline assembly: lane L's 16 bytes
 // land at lds_off + 16*L.  The compiler does not know this is a load, so it
