@@ -145,8 +145,9 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
             n_plain += plain[g].size();
             n_win += win[g].size();
         }
-        A->slab_ok = n_plain > 0 && (double)n_win <= 1.15 * (double)n_plain && A->slab_chunks < (1 << 14);
         A->slab_chunks = (K + shflbw::SLAB_KC - 1) / shflbw::SLAB_KC;
+        // the table word has 14 bits for a step's chunk
+        A->slab_ok = n_plain > 0 && (double)n_win <= 1.15 * (double)n_plain && A->slab_chunks < (1 << 14);
         const std::vector<std::vector<int>>& lens = A->slab_ok ? win : plain;
 
         // In the windowed layout every group gets a multiple of SLAB_UNROLL steps

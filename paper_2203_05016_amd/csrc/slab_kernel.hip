@@ -62,6 +62,7 @@ static_assert(SLAB_IPL * SLAB_LOADERS * 4 == SLAB_KC, "chunk must divide evenly"
 static_assert(SLAB_IPL * (SLAB_LEAD - 1) < 16, "vmcnt immediates below use the low four bits only");
 
 constexpr int SLAB_SPIN_LIMIT = 1 << 20;
+constexpr int SLAB_BUFFER_FLAGS = 0x00020000;     // last word of a raw buffer descriptor: untyped 32-bit data
 
 typedef __attribute__((address_space(3))) char* lds_char_ptr;
 
@@ -99,6 +100,7 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     constexpr int FLAGS_OFF = SCRATCH_OFF + GW * WAVE_BYTES;  // landed[4], progress[GW]
     constexpr int LDS_BYTES = FLAGS_OFF + 128;
     static_assert(SLAB_LOADERS + GW <= 32, "flag block");
+    static_assert((SLAB_LOADERS & (SLAB_LOADERS - 1)) == 0, "the landed counts are read with lane & (SLAB_LOADERS - 1)");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
     __shared__ __attribute__((aligned(1024))) char smem[LDS_BYTES];
 
@@ -235,8 +237,21 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     // register sets; step s uses set s % PD and refills it for step s + PD (the
     // index is clamped at the end, so the loads are unconditional).
     const int last = nsteps - 1;
-    const uint32_t* tabp = a.table + (long)sbeg * 64 + lane;
-    const half8* valp = a.A.values + (long)sbeg * RB * 64 + lane;
+    // Buffer loads: the descriptor holds the group's base address, the step's offset goes in a
+    // scalar register and the lane's in one vector register, so a load costs no vector
+    // arithmetic.  Offsets beyond the group's steps would read as zero.
+    typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+    const __amdgpu_buffer_rsrc_t tab_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint32_t*>(a.table + (long)sbeg * 64), 0, nsteps * 256, SLAB_BUFFER_FLAGS);
+    const __amdgpu_buffer_rsrc_t val_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<half8*>(a.A.values + (long)sbeg * RB * 64), 0, nsteps * RB * 1024, SLAB_BUFFER_FLAGS);
+    auto load_table = [&](int s) __attribute__((always_inline)) {
+        return __builtin_amdgcn_raw_buffer_load_b32(tab_rsrc, lane * 4, s * 256, 0);
+    };
+    auto load_weights = [&](int s, int rb) __attribute__((always_inline)) {
+        return __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, lane * 16,
+                                                                                (s * RB + rb) * 1024, 0));
+    };
     unsigned mt[PD];
     half8 mw[PD][RB];
 #pragma unroll
@@ -245,13 +260,14 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) mw[u][rb] = half8{0, 0, 0, 0, 0, 0, 0, 0};
         if (nsteps > 0) {
-            mt[u] = tabp[(long)u * 64];
+            mt[u] = load_table(u);
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) mw[u][rb] = valp[((long)u * RB + rb) * 64];
+            for (int rb = 0; rb < RB; ++rb) mw[u][rb] = load_weights(u, rb);
         }
     }
 
-    int cur = 0;  // chunk of the step in hand; every step of an earlier chunk is done
+    int cur = 0;   // chunk of the step in hand; every step of an earlier chunk is done
+    int seen = 0;  // chunks known to have landed (the least of the loaders' counts when last read)
     for (int s0 = 0; s0 < nsteps; s0 += PD) {
 #pragma unroll
         for (int u = 0; u < PD; ++u) {
@@ -263,8 +279,22 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
                 progress[wave] = e;
                 cur = e;
             }
-            for (int tries = 0; !reached(landed, SLAB_LOADERS, e + 1) && tries < SLAB_SPIN_LIMIT; ++tries)
-                __builtin_amdgcn_s_sleep(1);
+            if (seen < e + 1) {
+                // the flags are read only when the chunk is not already known to be in
+#pragma nounroll
+                for (int tries = 0; tries < SLAB_SPIN_LIMIT; ++tries) {
+                    const int v = landed[lane & (SLAB_LOADERS - 1)];
+                    int m = __builtin_amdgcn_readlane(v, 0);
+#pragma unroll
+                    for (int l = 1; l < SLAB_LOADERS; ++l) {
+                        const int o = __builtin_amdgcn_readlane(v, l);
+                        m = o < m ? o : m;
+                    }
+                    seen = m;
+                    if (m >= e + 1) break;
+                    __builtin_amdgcn_s_sleep(1);
+                }
+            }
             asm volatile("" ::: "memory");
 
             const int row0 = tab & 511, row1 = (tab >> 9) & 511;
@@ -294,9 +324,9 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
             }
             {
                 const int sn = (s0 + u + PD < nsteps) ? s0 + u + PD : last;
-                mt[u] = tabp[(long)sn * 64];
+                mt[u] = load_table(sn);
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb) mw[u][rb] = valp[((long)sn * RB + rb) * 64];
+                for (int rb = 0; rb < RB; ++rb) mw[u][rb] = load_weights(sn, rb);
             }
         }
     }
