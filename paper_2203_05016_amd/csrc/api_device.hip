@@ -39,6 +39,7 @@ int launch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long l
     SlabArgs a;
     a.A = view_of(A);
     a.table = reinterpret_cast<const uint32_t*>(static_cast<const char*>(A->dev_base) + A->off_table);
+    a.first_chunk = reinterpret_cast<const int32_t*>(static_cast<const char*>(A->dev_base) + A->off_iter);
     a.X = static_cast<const _Float16*>(X);
     a.Y = Y;
     a.ldx = ldx; a.ldy = ldy; a.N = N;
@@ -245,6 +246,7 @@ int shflbw_bind_device(shflbw_matrix* A, void* dev_buf, void* stream)
     const Part parts[] = {
         {A->off_rows, A->row_indices.data(), A->row_indices.size() * sizeof(int32_t)},
         {A->off_steps, A->step_ptr.data(), A->step_ptr.size() * sizeof(int32_t)},
+        {A->off_iter, A->first_chunk.data(), A->first_chunk.size() * sizeof(int32_t)},
         {A->off_cols, A->col_idx.data(), A->col_idx.size() * sizeof(int32_t)},
         {A->off_table, A->slab_table.data(), A->slab_table.size() * sizeof(uint32_t)},
         {A->off_vals, A->values.data(), A->values.size() * sizeof(uint16_t)},

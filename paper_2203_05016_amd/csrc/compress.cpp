@@ -137,17 +137,41 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
                 i = j;
             }
         };
-        std::vector<std::vector<int>> plain(G), win(G);
+        // The slab kernel learns a step's chunk from a 4-bit difference to the step
+        // before it (the group's first chunk is stored per group), so where two
+        // consecutive steps of the windowed layout lie more than 15 chunks apart,
+        // empty steps (length 0) are put between them, each carrying 15 chunks.
+        auto bridge_gaps = [&](const std::vector<int32_t>& c, std::vector<int>& lens, std::vector<int>& chunk) {
+            std::vector<int> out_len, out_chunk;
+            size_t t = 0;
+            int prev = -1;
+            for (int len : lens) {
+                t += (size_t)len;
+                const int e = c[t - 1] / shflbw::SLAB_KC;
+                if (prev >= 0)
+                    while (e - prev > shflbw::SLAB_MAX_CHUNK_STEP) {
+                        prev += shflbw::SLAB_MAX_CHUNK_STEP;
+                        out_len.push_back(0);
+                        out_chunk.push_back(prev);
+                    }
+                out_len.push_back(len);
+                out_chunk.push_back(e);
+                prev = e;
+            }
+            lens.swap(out_len);
+            chunk.swap(out_chunk);
+        };
+        std::vector<std::vector<int>> plain(G), win(G), win_chunk(G);
         size_t n_plain = 0, n_win = 0;
         for (int g = 0; g < G; ++g) {
             cut(cols[g], false, plain[g]);
             cut(cols[g], true, win[g]);
+            bridge_gaps(cols[g], win[g], win_chunk[g]);
             n_plain += plain[g].size();
             n_win += win[g].size();
         }
         A->slab_chunks = (K + shflbw::SLAB_KC - 1) / shflbw::SLAB_KC;
-        // the table word has 14 bits for a step's chunk
-        A->slab_ok = n_plain > 0 && (double)n_win <= 1.15 * (double)n_plain && A->slab_chunks < (1 << 14);
+        A->slab_ok = n_plain > 0 && (double)n_win <= 1.15 * (double)n_plain;
         const std::vector<std::vector<int>>& lens = A->slab_ok ? win : plain;
 
         // In the windowed layout every group gets a multiple of SLAB_UNROLL steps
@@ -171,6 +195,7 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
             const int32_t* rows = &A->row_indices[(size_t)g * V];
             size_t step = (size_t)A->step_ptr[g];
             size_t t = 0;
+            size_t nth = 0;   // position in the group's step list
             for (int len : lens[g]) {
                 uint16_t* dst = &A->values[step * (size_t)V * TK];
                 for (int j = 0; j < len; ++j, ++t) {
@@ -181,9 +206,10 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
                 }
                 if (A->slab_ok) {
                     // this step runs once the chunk of its last column is resident
-                    A->step_iter[step] = cols[g][t - 1] / shflbw::SLAB_KC;
+                    A->step_iter[step] = win_chunk[g][nth];
                 }
                 ++step;
+                ++nth;
             }
             // empty padding steps inherit the iteration of the step before them
             for (; step < (size_t)A->step_ptr[g + 1]; ++step)
@@ -192,27 +218,41 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
         }
 
         if (A->slab_ok) {
-            // lane map of the transposed LDS read, see slab_kernel.hip
+            // What each lane of the slab kernel needs to run a step (see slab_kernel.hip):
+            // the LDS byte addresses of its two transposed reads for the first
+            // instruction tile, and how many chunks the step lies past the one before.
             A->slab_table.resize(steps * 64);
-            for (size_t st = 0; st < steps; ++st)
-                for (int lane = 0; lane < 64; ++lane) {
-                    const int bl = lane >> 4, il = lane & 15;
-                    const int kq = (V == 16) ? (8 * bl + (il >> 2)) : (8 * (bl >> 1) + (il >> 2));
-                    uint32_t e = (uint32_t)A->step_iter[st] << 18;
-                    for (int h = 0; h < 2; ++h) {
-                        const int k = A->col_idx[st * TK + kq + 4 * h];
-                        const uint32_t row = k < 0 ? (uint32_t)shflbw::SLAB_ZERO_ROW
-                                                   : (uint32_t)(k % shflbw::SLAB_RING_ROWS);
-                        e |= row << (9 * h);
+            A->first_chunk.assign(G, 0);
+            const bool small = (V == 16);
+            for (int g = 0; g < G; ++g) {
+                int prev = 0;
+                for (size_t st = (size_t)A->step_ptr[g]; st < (size_t)A->step_ptr[g + 1]; ++st) {
+                    if (st == (size_t)A->step_ptr[g]) prev = A->first_chunk[g] = A->step_iter[st];
+                    const uint32_t d = (uint32_t)(A->step_iter[st] - prev);   // 0 .. SLAB_MAX_CHUNK_STEP
+                    prev = A->step_iter[st];
+                    for (int lane = 0; lane < 64; ++lane) {
+                        const int bl = lane >> 4, il = lane & 15;
+                        const int kq = small ? (8 * bl + (il >> 2)) : (8 * (bl >> 1) + (il >> 2));
+                        const int qc = small ? ((il & 3) >> 1) : (2 * (bl & 1) + ((il & 3) >> 1));
+                        const int qbyte = (il & 1) << 3;
+                        uint32_t word = (d & 7u) | ((d >> 3) << 31);
+                        for (int h = 0; h < 2; ++h) {
+                            const int k = A->col_idx[st * TK + kq + 4 * h];
+                            const int row = k < 0 ? shflbw::SLAB_ZERO_ROW : k % shflbw::SLAB_RING_ROWS;
+                            const uint32_t addr = (uint32_t)(row * shflbw::SLAB_ROW_BYTES + qbyte +
+                                                             ((qc ^ ((row & 7) << 1)) << 4));
+                            word |= (addr >> 3) << (h ? 17 : 3);
+                        }
+                        A->slab_table[st * 64 + lane] = word;
                     }
-                    A->slab_table[st * 64 + lane] = e;
                 }
+            }
         }
 
         A->off_rows = 0;
         A->off_steps = shflbw::align256(A->off_rows + sizeof(int32_t) * (size_t)M);
         A->off_iter = shflbw::align256(A->off_steps + sizeof(int32_t) * (size_t)(G + 1));
-        A->off_cols = shflbw::align256(A->off_iter);
+        A->off_cols = shflbw::align256(A->off_iter + sizeof(int32_t) * A->first_chunk.size());
         A->off_table = shflbw::align256(A->off_cols + sizeof(int32_t) * A->col_idx.size());
         A->off_vals = shflbw::align256(A->off_table + sizeof(uint32_t) * A->slab_table.size());
         A->dev_bytes = shflbw::align256(A->off_vals + sizeof(uint16_t) * A->values.size());

@@ -26,10 +26,15 @@
 // would reach one chunk more is cut short and padded, and every group's step
 // count is rounded up to a multiple of SLAB_UNROLL with empty steps.
 // slab_table holds, per step and lane, what the slab kernel needs to run the
-// step: bits 0-8 and 9-17 are the LDS ring rows (column mod SLAB_RING_ROWS,
-// or SLAB_ZERO_ROW for padding) of the lane's two transposed reads, bits 18-31
-// the chunk of the step's last column (the step may run once that chunk is
-// resident).
+// step: bits 3-16 and 17-30 are the LDS byte addresses, divided by 8, of the
+// lane's two transposed reads for the first instruction tile (row of the ring
+// = column mod SLAB_RING_ROWS, or SLAB_ZERO_ROW for padding; the swizzled
+// 16-byte slot inside the row that the lane's position in the operand asks
+// for); bits 0-2 and 31 hold, as a 4-bit number, how many chunks the step's
+// last column lies past that of the group's previous step (the step may run
+// once that chunk is resident).  first_chunk holds the chunk of each group's
+// first step.  Steps more than SLAB_MAX_CHUNK_STEP chunks apart are bridged by
+// empty steps.
 //
 // values: for each k-step, for each 32-row block rb of the group (one block
 // when V = 16), 64 lanes x 8 binary16 in the operand order of the
@@ -48,6 +53,7 @@ struct shflbw_matrix {
     int slab_chunks = 0;               // C = ceil(K / SLAB_KC)
     std::vector<int32_t> step_iter;    // steps, only when slab_ok: chunk of each step's last column
     std::vector<uint32_t> slab_table;  // steps*64, only when slab_ok (see above)
+    std::vector<int32_t> first_chunk;  // G, only when slab_ok: chunk of each group's first step
     std::vector<uint16_t> values;      // steps*V*TK binary16 bit patterns
 
     // device image (caller-owned buffer), byte offsets of the sections
@@ -73,7 +79,10 @@ constexpr int SLAB_LEAD = SHFLBW_SLAB_LEAD;      // chunks in flight ahead of th
 constexpr int SLAB_RING_ROWS = SLAB_KC * (SLAB_WINDOW + SLAB_LEAD);  // rows of X resident in LDS; row of column k = k % RING_ROWS
 constexpr int SLAB_ZERO_ROW = SLAB_RING_ROWS;                       // one extra all-zero row for padded slots
 constexpr int SLAB_UNROLL = 4;                                      // steps per unrolled batch of the slab kernel
-static_assert(SLAB_ZERO_ROW < 512, "ring rows are stored in 9 bits");
+constexpr int SLAB_TN = 128;                                        // output columns per workgroup of the slab kernel
+constexpr int SLAB_ROW_BYTES = SLAB_TN * 2;                         // one staged row of X in LDS
+constexpr int SLAB_MAX_CHUNK_STEP = 15;                             // largest chunk difference a table word can hold
+static_assert((SLAB_ZERO_ROW + 1) * SLAB_ROW_BYTES / 8 <= (1 << 14), "LDS addresses are stored in 14 bits, in units of 8 bytes");
 int fail(int status, const std::string& detail);  // records the thread-local text, returns status
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 }  // namespace shflbw

@@ -29,8 +29,14 @@
 // bounded: a wavefront that does not see its condition within about a
 // million tries goes on regardless (wrong numbers instead of a hang).
 //
-// Per step and lane the compressor stores one table word: the LDS ring rows
-// (column mod 384) of the lane's two transposed reads and the step's chunk.
+// Per step and lane the compressor stores one table word: the LDS byte
+// addresses of the lane's two transposed reads for the first instruction tile
+// (ring row = column mod 384, swizzled slot included; the other tiles differ
+// from it in the tile's bits only, one exclusive-or each), and by how many
+// chunks the step lies past the one before it.  Nothing but two masks is left
+// to compute per step: the loop is bound by instruction issue (address
+// arithmetic and matrix instructions share the vector issue port), not by the
+// traffic.
 //
 // Algorithm 1's parts: BulkLoadMeta = each step's weight tile and table word
 // fetched into registers four steps ahead (two for V = 64, whose two row
@@ -51,9 +57,7 @@
 
 namespace shflbw {
 
-constexpr int SLAB_TN = 128;                       // output columns per workgroup
 constexpr int SLAB_STAGES = SLAB_WINDOW + SLAB_LEAD;
-constexpr int SLAB_ROW_BYTES = SLAB_TN * 2;        // 256 B per staged row
 constexpr int SLAB_STAGE_BYTES = SLAB_KC * SLAB_ROW_BYTES;
 constexpr int SLAB_X_BYTES = (SLAB_ZERO_ROW + 1) * SLAB_ROW_BYTES;  // ring + the all-zero row
 constexpr int SLAB_LOADERS = 4;                    // loader wavefronts per workgroup
@@ -78,7 +82,8 @@ __device__ __forceinline__ void meta_dma16(const void* g, unsigned lds_off)
 }
 struct SlabArgs {
     PackedView A;
-    const uint32_t* table;    // steps*64 table words (ring rows, chunk)
+    const uint32_t* table;    // steps*64 table words (LDS addresses of the lane's reads, chunk difference)
+    const int32_t* first_chunk;  // chunk of each group's first step
     const _Float16* X;
     void* Y;
     long ldx, ldy, N;
@@ -200,11 +205,6 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     const int sbeg = a.A.step_ptr[g];
     const int nsteps = a.A.step_ptr[g + 1] - sbeg;  // a multiple of PD
 
-    const int bl = lane >> 4, il = lane & 15;
-    // 16-byte chunk (before the tile offset) and byte inside it that this lane reads
-    const int qc = SMALL ? ((il & 3) >> 1) : (2 * (bl & 1) + ((il & 3) >> 1));
-    const int qbyte = (il & 1) << 3;
-
     floatx16 acc32[SMALL ? 1 : RB][SMALL ? 1 : NT];
     floatx4 acc16[SMALL ? NT : 1];
     if (SMALL) {
@@ -256,23 +256,24 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     half8 mw[PD][RB];
 #pragma unroll
     for (int u = 0; u < PD; ++u) {
-        mt[u] = 0;
+        // a group without steps has an empty descriptor: these read as zero
+        mt[u] = load_table(u);
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) mw[u][rb] = half8{0, 0, 0, 0, 0, 0, 0, 0};
-        if (nsteps > 0) {
-            mt[u] = load_table(u);
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) mw[u][rb] = load_weights(u, rb);
-        }
+        for (int rb = 0; rb < RB; ++rb) mw[u][rb] = load_weights(u, rb);
+        // keep the sets in issue order: the loop's wait counts assume set 0 is the oldest
+        __builtin_amdgcn_sched_barrier(0);
     }
 
-    int cur = 0;   // chunk of the step in hand; every step of an earlier chunk is done
+    int chunk = a.first_chunk[g];   // of the step in hand, from the table's differences
+    int cur = 0;   // chunk last published; every step of an earlier chunk is done
     int seen = 0;  // chunks known to have landed (the least of the loaders' counts when last read)
     for (int s0 = 0; s0 < nsteps; s0 += PD) {
 #pragma unroll
         for (int u = 0; u < PD; ++u) {
             const unsigned tab = mt[u];
-            const int e = __builtin_amdgcn_readfirstlane(tab >> 18);
+            const unsigned head = __builtin_amdgcn_readfirstlane(tab);
+            chunk += (head & 7) | ((head >> 31) << 3);
+            const int e = chunk;
             if (e != cur) {
                 // this wavefront's reads of chunks below e - WINDOW + 1 are over
                 asm volatile("" ::: "memory");
@@ -297,18 +298,15 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
             }
             asm volatile("" ::: "memory");
 
-            const int row0 = tab & 511, row1 = (tab >> 9) & 511;
-            const int base0 = row0 * SLAB_ROW_BYTES + qbyte, swz0 = (row0 & 7) << 1;
-            const int base1 = row1 * SLAB_ROW_BYTES + qbyte, swz1 = (row1 & 7) << 1;
+            const unsigned addr0 = tab & 0x1fff8u, addr1 = (tab >> 14) & 0x1fff8u;
             // all transposed reads of the step go out before the first product
             half8 x[NT];
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                const int q = (SMALL ? 2 * t : 4 * t) + qc;
-                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (lds_short4_ptr)(smem + base0 + ((q ^ swz0) << 4)));
-                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (lds_short4_ptr)(smem + base1 + ((q ^ swz1) << 4)));
+                // tile t: 16-byte slot (SMALL ? 2t : 4t) further on, before the swizzle
+                constexpr int TILE_BITS = SMALL ? 32 : 64;
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(smem + (addr0 ^ (t * TILE_BITS))));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(smem + (addr1 ^ (t * TILE_BITS))));
                 half4 l4 = __builtin_bit_cast(half4, lo), h4 = __builtin_bit_cast(half4, hi);
                 x[t] = half8{l4[0], l4[1], l4[2], l4[3], h4[0], h4[1], h4[2], h4[3]};
             }
