@@ -53,6 +53,22 @@ def test_empty_group_and_all_empty():
     assert not B.decompress().any()
 
 
+@pytest.mark.parametrize("V", [16, 32])
+def test_distant_column_bands_round_trip(V):
+    """Two bands of kept columns far apart: the windowed layout bridges them
+    with empty k-steps, which must not show in the columns or the weights."""
+    p = synth.make_spmm(3 * V, 2560, 8, V, 0.0, seed=23 + V)
+    p.mask[:, 512:2048] = 0
+    p.mask[p.perm[V:2 * V], :448] = 0
+    A = binding.compress(p.W, p.mask, p.perm, V)
+    band = np.concatenate([np.arange(512), np.arange(2048, 2560)])
+    assert np.array_equal(A.group_columns(0), band)
+    assert np.array_equal(A.group_columns(1), band[band >= 448])
+    assert A.info()["nnz"] == int(p.mask.sum())
+    want = np.where(p.mask != 0, p.W, np.float16(0))
+    assert np.array_equal(A.decompress().view(np.uint16), want.view(np.uint16))
+
+
 def test_null_mask_keeps_vectors_with_any_nonzero():
     p = synth.make_spmm(32, 24, 4, 16, 0.5, seed=8)
     Wm = np.where(p.mask != 0, p.W, np.float16(0))

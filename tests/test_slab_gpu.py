@@ -91,3 +91,17 @@ def test_slab_config2_ffn_sampled():
     cols = np.unique(np.concatenate([[0, 127, 128, p.N - 1], rng.choice(p.N, 60, replace=False)]))
     Yr, S = c_oracle.spmm(p.W, p.mask, np.ascontiguousarray(p.X[:, cols]))
     assert_within_scaled_tolerance(Y[:, cols], Yr, S, what="slab config2 sample")
+
+
+def test_slab_distant_steps_are_bridged():
+    """Every group keeps two bands of columns 24 chunks apart (further than the
+    table's 4-bit chunk difference reaches, so the compressor puts an empty
+    step between them), and one group starts late (its first chunk is not 0)."""
+    announce("slab distant steps")
+    p = synth.make_spmm(12 * 32, 2560, 264, 32, 0.0, seed=157)
+    p.mask[:, 512:2048] = 0
+    p.mask[p.perm[32:64], :448] = 0
+    for out_dtype in ("float16", "float32"):
+        Y = run_spmm(p, kernel=SLAB, out_dtype=out_dtype)
+        Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+        assert_within_scaled_tolerance(Y, Yr, S, what="slab distant steps")
