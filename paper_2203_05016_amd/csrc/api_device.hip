@@ -307,6 +307,16 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
         return dispatch_slab<float, false>(A, X, (long)ldx, Y, (long)ldy, (long)N, st);
     }
     if (aligned) {
+        // X behind a buffer descriptor where 24-bit offset arithmetic and a 32-bit range cover it
+        const int64_t xbytes = ((int64_t)A->K - 1) * ldx * 2 + N * 2;
+        if (A->K < (1 << 24) && ldx * 2 < (1 << 24) && xbytes + 2 * ldx * 2 < ((int64_t)1 << 32) - 64) {
+            GeomLinearBuf g;
+            g.X = static_cast<const _Float16*>(X);
+            g.Y = Y;
+            g.ldx = (long)ldx; g.ldy = (long)ldy; g.N = (long)N;
+            g.xbytes = (unsigned)xbytes;
+            return dispatch_out(A, g, (long)N, ydtype, st);
+        }
         GeomLinear<true> g{static_cast<const _Float16*>(X), Y, (long)ldx, (long)ldy, (long)N};
         return dispatch_out(A, g, (long)N, ydtype, st);
     }

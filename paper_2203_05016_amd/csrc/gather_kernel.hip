@@ -141,6 +141,54 @@ struct GeomLinear {
     }
 };
 
+// The aligned linear layer again, with X behind a buffer descriptor: a load's
+// address is one 24-bit multiply-add in a vector register (byte offset of the
+// row plus the lane's column offset) instead of 64-bit arithmetic, and the
+// descriptor's range check stands in for the two conditions - a padded slot
+// (column -1) and a lane beyond N get an offset past the end and read as zero.
+// The host uses it when K and 2*ldx are below 2^24 and X spans less than 4 GiB.
+constexpr int GATHER_BUFFER_FLAGS = 0x00020000;   // last word of a raw buffer descriptor: untyped 32-bit data
+struct GeomLinearBuf {
+    const _Float16* X;
+    void* Y;
+    long ldx, ldy, N;
+    unsigned xbytes;          // (K-1)*ldx*2 + N*2: what the descriptor covers
+    __amdgpu_buffer_rsrc_t xd;
+    unsigned ldx2, ln2;
+    // beyond every descriptor the host admits, and 16 bytes from there do not wrap
+    static constexpr unsigned PAST_END = 0xffffffe0u;
+
+    __device__ __forceinline__ void init(long n)
+    {
+        xd = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(X), 0, (int)xbytes, GATHER_BUFFER_FLAGS);
+        ldx2 = (unsigned)ldx * 2u;
+        ln2 = n < N ? (unsigned)n * 2u : PAST_END;
+    }
+
+    __device__ __forceinline__ half8 load8(int col, long) const
+    {
+        typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+        // a lane beyond N keeps its offset past the end whatever the column
+        unsigned off = __umul24((unsigned)col, ldx2) + ln2;
+        off = (col < 0 || ln2 == PAST_END) ? PAST_END : off;
+        return __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(xd, (int)off, 0, 0));
+    }
+
+    template <typename OutT, int CNT>
+    __device__ __forceinline__ void store(int row, long n, const OutT* vals) const
+    {
+        OutT* p = static_cast<OutT*>(Y) + (long)row * ldy + n;
+        if (n < N) {
+            typedef OutT vec_t __attribute__((ext_vector_type(CNT)));
+            vec_t v;
+#pragma unroll
+            for (int e = 0; e < CNT; ++e) v[e] = vals[e];
+            // the output is not read again by this kernel: keep it from displacing X and W in the L2
+            __builtin_nontemporal_store(v, reinterpret_cast<vec_t*>(p));
+        }
+    }
+};
+
 // Convolution as implicit GEMM (Section 4.1): k = (c*R + r)*S + s, and
 // n = (b*Ho + y)*Wo + x for NCHW or n = (y*Wo + x)*B + b for CHWN.  This is
 // the general element-wise form; the unfolded matrix never exists in memory.
@@ -300,17 +348,25 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
     half8 xr[PD][NLD];
     half8 wr[PD][RB];
 
+    // Column indices and weights of the wavefront's steps through buffer descriptors: the
+    // step's offset is a scalar register, the lane's a constant vector register.
+    typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+    typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+    const __amdgpu_buffer_rsrc_t col_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int32_t*>(A.col_idx + (long)sbeg * TK), 0, nsteps * TK * 4, GATHER_BUFFER_FLAGS);
+    const __amdgpu_buffer_rsrc_t val_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<half8*>(A.values + (long)sbeg * RB * 64), 0, nsteps * RB * 1024, GATHER_BUFFER_FLAGS);
     auto load_cols = [&](int step, int (&c)[NLD]) {
-        const int32_t* p = A.col_idx + (long)(sbeg + step) * TK + lrow;
         if (NLD == 4) {
-            intx4 v = *reinterpret_cast<const intx4*>(p);
-            c[0] = v[0]; c[1] = v[1]; c[2] = v[2]; c[3] = v[3];
+            uint4v v = __builtin_amdgcn_raw_buffer_load_b128(col_rsrc, lrow * 4, step * TK * 4, 0);
+            c[0] = (int)v[0]; c[1] = (int)v[1]; c[2] = (int)v[2]; c[3] = (int)v[3];
         } else if (NLD == 2) {
-            intx2 v = *reinterpret_cast<const intx2*>(p);
-            c[0] = v[0]; c[1] = v[1];
+            uint2v v = __builtin_amdgcn_raw_buffer_load_b64(col_rsrc, lrow * 4, step * TK * 4, 0);
+            c[0] = (int)v[0]; c[1] = (int)v[1];
         } else {
 #pragma unroll
-            for (int i = 0; i < NLD; ++i) c[i] = p[i];
+            for (int i = 0; i < NLD; ++i)
+                c[i] = (int)__builtin_amdgcn_raw_buffer_load_b32(col_rsrc, (lrow + i) * 4, step * TK * 4, 0);
         }
     };
     auto load_x = [&](const int (&c)[NLD], half8 (&x)[NLD]) {
@@ -318,9 +374,10 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
         for (int i = 0; i < NLD; ++i) x[i] = geom.load8(c[i], ln);
     };
     auto load_w = [&](int step, half8 (&w)[RB]) {
-        const half8* p = A.values + ((long)(sbeg + step) * RB) * 64 + lane;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) w[rb] = p[rb * 64];
+        for (int rb = 0; rb < RB; ++rb)
+            w[rb] = __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, lane * 16,
+                                                                                    (step * RB + rb) * 1024, 0));
     };
 
 #pragma unroll
