@@ -89,6 +89,33 @@ def test_leading_dimensions_and_misaligned_bases():
         assert_within_scaled_tolerance(Y, Yr, S, what="ld=%d off=%d" % (pad_ld, offset))
 
 
+def test_very_long_leading_dimension_takes_plain_addressing():
+    """Rows of X and Y 16 MiB apart: beyond what the gather kernel's 24-bit
+    offset arithmetic covers, so the aligned path with 64-bit addresses runs
+    (every smaller aligned case goes through the buffer-descriptor path)."""
+    import torch
+    from paper_2203_05016_amd import binding
+    from gpu_util import to_device, to_host
+    announce("long ld")
+    p = synth.make_spmm(64, 40, 72, 32, 0.5, seed=77)
+    ld = (1 << 23) + 8
+    A = binding.compress(p.W, p.mask, p.perm, p.V).bind_device("cuda:0")
+    Xbuf = torch.zeros(p.K * ld, dtype=torch.float16, device="cuda:0")
+    Xd = Xbuf.view(p.K, ld)[:, :p.N]
+    Xd.copy_(to_device(p.X))
+    Ybuf = torch.full((p.M * ld,), float("nan"), dtype=torch.float16, device="cuda:0")
+    Yd = Ybuf.view(p.M, ld)[:, :p.N]
+    A.spmm(Xd, Yd)
+    torch.cuda.synchronize()
+    Y = to_host(Yd.contiguous())
+    # nothing next to the window was written
+    assert torch.isnan(Ybuf.view(p.M, ld)[:, p.N:p.N + 64]).all().item()
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    assert_within_scaled_tolerance(Y, Yr, S, what="long leading dimension")
+    del Xbuf, Ybuf, Xd, Yd
+    torch.cuda.empty_cache()
+
+
 def test_dense_identity_is_gemm():
     """Sparsity 0 with the identity permutation: the kernel is a dense GEMM."""
     announce("dense identity")
