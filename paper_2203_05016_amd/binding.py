@@ -99,18 +99,21 @@ def _host_ptr(a):
 def _stream_ptr(stream):
     import torch
     s = torch.cuda.current_stream() if stream is None else stream
-    return ctypes.c_void_p(s.cuda_stream)
+    return s.cuda_stream
+
+
+_YDTYPE = None   # torch dtype -> shflbw_dtype, filled on first use (torch is imported lazily)
 
 
 def _ydtype(t):
-    import torch
-    if t.dtype == torch.float16:
-        return F16
-    if t.dtype == torch.bfloat16:
-        return BF16
-    if t.dtype == torch.float32:
-        return F32
-    raise TypeError("output tensor must be float16, bfloat16 or float32")
+    global _YDTYPE
+    if _YDTYPE is None:
+        import torch
+        _YDTYPE = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
+    try:
+        return _YDTYPE[t.dtype]
+    except KeyError:
+        raise TypeError("output tensor must be float16, bfloat16 or float32") from None
 
 
 class Matrix:
@@ -121,10 +124,14 @@ class Matrix:
         self._h = handle
         self._dev = None
         self.bf16 = bf16   # operand format: bfloat16 instead of float16
+        self._info = None  # what shflbw_info reports: fixed once the matrix is packed
+        self._odt = None
 
     def _operand_dtype(self):
-        import torch
-        return torch.bfloat16 if self.bf16 else torch.float16
+        if self._odt is None:
+            import torch
+            self._odt = torch.bfloat16 if self.bf16 else torch.float16
+        return self._odt
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
@@ -133,11 +140,13 @@ class Matrix:
 
     # -- host side
     def info(self):
-        M, K, V, G = (ctypes.c_int() for _ in range(4))
-        nnz, sp = ctypes.c_int64(), ctypes.c_double()
-        _check(lib().shflbw_info(self._h, M, K, V, G, nnz, sp))
-        return dict(M=M.value, K=K.value, V=V.value, groups=G.value, nnz=nnz.value,
-                    sparsity=sp.value)
+        if self._info is None:
+            M, K, V, G = (ctypes.c_int() for _ in range(4))
+            nnz, sp = ctypes.c_int64(), ctypes.c_double()
+            _check(lib().shflbw_info(self._h, M, K, V, G, nnz, sp))
+            self._info = dict(M=M.value, K=K.value, V=V.value, groups=G.value, nnz=nnz.value,
+                              sparsity=sp.value)
+        return dict(self._info)
 
     def row_indices(self):
         out = np.empty(self.info()["M"], dtype=np.int32)
@@ -176,18 +185,19 @@ class Matrix:
     def spmm(self, X, Y=None, out_dtype=None, stream=None):
         """Y = (W . mask) X for a device tensor X of shape (K, N) in the
         matrix's operand format (float16, or bfloat16)."""
-        import torch
         if X.dtype != self._operand_dtype() or X.dim() != 2 or X.stride(1) != 1 and X.shape[1] > 1:
             raise TypeError("X must be a 2-D %s tensor with unit column stride" % self._operand_dtype())
-        N = X.shape[1]
+        K, N = X.shape
         if Y is None:
+            import torch
             Y = torch.empty((self.info()["M"], N), dtype=out_dtype or self._operand_dtype(),
                             device=X.device)
-        ldx = X.stride(0) if X.shape[0] > 1 else max(N, 1)
+        ldx = X.stride(0) if K > 1 else max(N, 1)
         ldy = Y.stride(0) if Y.shape[0] > 1 else max(N, 1)
-        _check(lib().shflbw_spmm(self._h, ctypes.c_void_p(X.data_ptr()), ldx,
-                                 ctypes.c_void_p(Y.data_ptr()), ldy, N, _ydtype(Y),
-                                 _stream_ptr(stream)))
+        rc = lib().shflbw_spmm(self._h, X.data_ptr(), ldx, Y.data_ptr(), ldy, N, _ydtype(Y),
+                               _stream_ptr(stream))
+        if rc < 0:
+            _check(rc)
         return Y
 
     def conv2d(self, inp, R, S, stride=(1, 1), pad=(0, 0), layout="NCHW", out=None,
@@ -202,12 +212,11 @@ class Matrix:
             C, H, W, B = inp.shape
         Ho = (H + 2 * pad[0] - R) // stride[0] + 1
         Wo = (W + 2 * pad[1] - S) // stride[1] + 1
-        Cout = self.info()["M"]
-        shape = (B, Cout, Ho, Wo) if layout == "NCHW" else (Cout, Ho, Wo, B)
         if out is None:
+            Cout = self.info()["M"]
+            shape = (B, Cout, Ho, Wo) if layout == "NCHW" else (Cout, Ho, Wo, B)
             out = torch.empty(shape, dtype=out_dtype or self._operand_dtype(), device=inp.device)
-        _check(lib().shflbw_conv2d(self._h, ctypes.c_void_p(inp.data_ptr()),
-                                   ctypes.c_void_p(out.data_ptr()), B, C, H, W, R, S,
+        _check(lib().shflbw_conv2d(self._h, inp.data_ptr(), out.data_ptr(), B, C, H, W, R, S,
                                    stride[0], stride[1], pad[0], pad[1],
                                    NCHW if layout == "NCHW" else CHWN, _ydtype(out),
                                    _stream_ptr(stream)))
