@@ -25,6 +25,44 @@ inline size_t value_slot(int V, int i, int j)
     int lane = (j / 8) * 32 + r;
     return ((size_t)rb * 64 + lane) * 8 + (j % 8);
 }
+
+// Order of a k-step's columns over its slots.  Any order is a valid packing (the weights follow
+// their columns); this one serves the slab kernel's transposed LDS reads: one read covers, per
+// 32 lanes, the rows of one slot group - 4 slots (V >= 32), or 8 (V = 16: slots 0-3 with 8-11,
+// 4-7 with 12-15, and so on) - and is free of bank conflicts when the group's columns differ in
+// their low two (three) bits, which pick the bank group through the row swizzle.  Columns are
+// therefore dealt to the groups one residue class at a time, largest class first.
+// c: the step's columns, ascending; slot_of[j]: slot of c[j].
+void arrange_step(const int32_t* c, int len, int V, int* slot_of)
+{
+    const bool small = (V == 16);
+    const int GS = small ? 8 : 4, TK = small ? 32 : 16;
+    int slots[32];   // slots in group order
+    for (int grp = 0, n = 0; grp < TK / GS; ++grp)
+        for (int i = 0; i < GS; ++i)
+            slots[n++] = small ? 16 * (grp >> 1) + 4 * (grp & 1) + (i < 4 ? i : 4 + i) : 4 * grp + i;
+    int bucket[8][32], count[8] = {0};
+    for (int j = 0; j < len; ++j) {
+        const int cls = c[j] & (GS - 1);
+        bucket[cls][count[cls]++] = j;
+    }
+    int taken[8] = {0};
+    for (int n = 0; n < len;) {
+        // one group: at most one column of each class while classes last, then whatever is left
+        bool used[8] = {false};
+        for (int i = 0; i < GS && n < len; ++i) {
+            int best = -1;
+            for (int pass = 0; pass < 2 && best < 0; ++pass)
+                for (int cls = 0; cls < GS; ++cls) {
+                    const int left = count[cls] - taken[cls];
+                    if (left <= 0 || (pass == 0 && used[cls])) continue;
+                    if (best < 0 || left > count[best] - taken[best]) best = cls;
+                }
+            used[best] = true;
+            slot_of[bucket[best][taken[best]++]] = slots[n++];
+        }
+    }
+}
 }  // namespace
 
 namespace shflbw {
@@ -198,11 +236,13 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
             size_t nth = 0;   // position in the group's step list
             for (int len : lens[g]) {
                 uint16_t* dst = &A->values[step * (size_t)V * TK];
+                int slot_of[32];
+                arrange_step(&cols[g][t], len, V, slot_of);
                 for (int j = 0; j < len; ++j, ++t) {
                     const int k = cols[g][t];
-                    A->col_idx[step * TK + j] = k;
+                    A->col_idx[step * TK + slot_of[j]] = k;
                     for (int i = 0; i < V; ++i)
-                        dst[value_slot(V, i, j)] = Wb[(size_t)rows[i] * ldw + k];
+                        dst[value_slot(V, i, slot_of[j])] = Wb[(size_t)rows[i] * ldw + k];
                 }
                 if (A->slab_ok) {
                     // this step runs once the chunk of its last column is resident
@@ -240,7 +280,7 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
                             const int k = A->col_idx[st * TK + kq + 4 * h];
                             const int row = k < 0 ? shflbw::SLAB_ZERO_ROW : k % shflbw::SLAB_RING_ROWS;
                             const uint32_t addr = (uint32_t)(row * shflbw::SLAB_ROW_BYTES + qbyte +
-                                                             ((qc ^ ((row & 7) << 1)) << 4));
+                                                             ((qc ^ shflbw::slab_swizzle(row)) << 4));
                             word |= (addr >> 3) << (h ? 17 : 3);
                         }
                         A->slab_table[st * 64 + lane] = word;
@@ -300,6 +340,7 @@ int shflbw_group_columns(const shflbw_matrix* A, int g, int32_t* cols, int cap)
     int n = 0;
     for (size_t t = 0; t < slots; ++t)
         if (src[t] >= 0) cols[n++] = src[t];
+    std::sort(cols, cols + n);   // inside a step the columns are not stored in ascending order
     return n;
 }
 

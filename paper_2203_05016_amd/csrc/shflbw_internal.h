@@ -83,6 +83,13 @@ constexpr int SLAB_TN = 128;                                        // output co
 constexpr int SLAB_ROW_BYTES = SLAB_TN * 2;                         // one staged row of X in LDS
 constexpr int SLAB_MAX_CHUNK_STEP = 15;                             // largest chunk difference a table word can hold
 static_assert((SLAB_ZERO_ROW + 1) * SLAB_ROW_BYTES / 8 <= (1 << 14), "LDS addresses are stored in 14 bits, in units of 8 bytes");
+// Swizzle of the 16-byte slots inside a staged row of X (the loader stores logical slot q of
+// ring row r at slot q ^ slab_swizzle(r); the table's read addresses include it).  One
+// transposed read covers, per 32 lanes, four rows of a step and a 64-byte window (four slots,
+// 16 banks) of each: bits 2-3 of the value move the window, and they come from the row's low
+// two bits so that four consecutive rows - every quad of a dense matrix - land in four
+// different bank groups; bit 1 varies with the next row bit.
+constexpr int slab_swizzle(int r) { return ((r & 3) << 2) | (((r >> 2) & 1) << 1); }
 int fail(int status, const std::string& detail);  // records the thread-local text, returns status
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 }  // namespace shflbw

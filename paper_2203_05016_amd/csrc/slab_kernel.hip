@@ -156,7 +156,7 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
             for (int i = 0; i < SLAB_IPL; ++i) {
                 const int piece = lw * SLAB_IPL + i;
                 const int r = 4 * piece + lrow;                       // row inside the chunk
-                const int q = lpos ^ ((r & 7) << 1);                  // column chunk for this slot
+                const int q = lpos ^ slab_swizzle(r);                 // column chunk for this slot
                 int row = c * SLAB_KC + r;
                 row = row < a.K ? row : a.K - 1;
                 long n = n0 + q * 8;
