@@ -372,8 +372,17 @@ extern "C" int shflbw_layernorm_transpose(const void* x, int64_t ldx, const void
                          : (const void*)&layernorm_transpose_resident_kernel<true, 32>)
             : (tok == 64 ? (const void*)&layernorm_transpose_resident_kernel<false, 64>
                          : (const void*)&layernorm_transpose_resident_kernel<false, 32>);
-        hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (ea != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(ea));
+        // the attribute is raised once per kernel and device
+        static thread_local int raised_on[4] = {-1, -1, -1, -1};
+        const int which = (dtype == SHFLBW_BF16 ? 2 : 0) + (tok == 64 ? 1 : 0);
+        int dev = 0;
+        hipError_t ea = hipGetDevice(&dev);
+        if (ea != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(ea));
+        if (raised_on[which] != dev) {
+            ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (ea != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(ea));
+            raised_on[which] = dev;
+        }
         const dim3 grid((unsigned)rwgs), block(64 * LN_WAVES);
         if (dtype == SHFLBW_BF16) {
             if (tok == 64) hipLaunchKernelGGL((layernorm_transpose_resident_kernel<true, 64>), grid, block, bytes, st, a, pitch);
