@@ -239,8 +239,8 @@ def main():
                     help="what --pmc launches three times after the calibration copy")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards over N "
-              "without any exchange, see DESIGN.md", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); with more, the product would "
+              "shard over the columns of X without any exchange between GPUs", file=sys.stderr)
         sys.exit(2)
 
     import torch
