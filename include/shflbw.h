@@ -65,7 +65,8 @@ typedef enum {
     SHFLBW_ERR_NOT_ON_DEVICE = -6, /* spmm/conv2d before shflbw_bind_device */
     SHFLBW_ERR_HIP = -7,           /* a HIP runtime call failed; text in shflbw_last_error() */
     SHFLBW_ERR_NO_MEMORY = -8,     /* host allocation failed */
-    SHFLBW_ERR_BAD_OPTION = -9     /* unknown tuning value */
+    SHFLBW_ERR_BAD_OPTION = -9,    /* unknown tuning value */
+    SHFLBW_ERR_HANDOVER = -10      /* a kernel's bounded wait ran out; see shflbw_device_status */
 } shflbw_status;
 
 /*
@@ -144,6 +145,23 @@ int shflbw_bind_device(shflbw_matrix* A, void* dev_buf, void* stream);
  * tile_n: 0 = automatic, else the number of output columns one wavefront of
  * the gather kernel owns (64 or 128). */
 int shflbw_set_tuning(shflbw_matrix* A, int kernel, int tile_n);
+
+/* The shared-slab kernel hands chunks of X from its loader wavefronts to its
+ * compute wavefronts through flags in LDS (Alg. 1's pipeline, without
+ * workgroup barriers).  Every wait on a flag is bounded: a wavefront that has
+ * polled `tries` times goes on regardless, so a lost hand-over yields wrong
+ * numbers, never a hang - and it sets a word in the matrix's device buffer.
+ *
+ * shflbw_device_status: waits for `stream`, reads that word back and clears
+ *   it.  SHFLBW_OK if no wait ran out in any launch on this matrix since the
+ *   last call (or since shflbw_bind_device); SHFLBW_ERR_HANDOVER otherwise:
+ *   results of those launches are not to be trusted.  Synchronises the
+ *   stream; meant for tests and for a check per batch, not per launch.
+ * shflbw_set_wait_limit: polls per wait before a wavefront gives up (default
+ *   2^20, about 50 ms).  tries >= 0; 0 makes every wait give up at once, which
+ *   is how the tests force the condition (every kernel still ends normally). */
+int shflbw_device_status(shflbw_matrix* A, void* stream);
+int shflbw_set_wait_limit(shflbw_matrix* A, int tries);
 
 /*
  * Linear layer (Algorithm 1: BulkLoadMeta / StitchTile / WarpMMA loop, then

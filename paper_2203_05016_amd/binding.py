@@ -22,8 +22,8 @@ _lib = None
 EXPORTS = [
     "shflbw_compress", "shflbw_pattern_search", "shflbw_destroy", "shflbw_info", "shflbw_row_indices",
     "shflbw_group_columns", "shflbw_decompress", "shflbw_device_bytes", "shflbw_bind_device",
-    "shflbw_set_tuning", "shflbw_spmm", "shflbw_conv2d", "shflbw_layernorm_transpose",
-    "shflbw_status_string", "shflbw_last_error",
+    "shflbw_set_tuning", "shflbw_device_status", "shflbw_set_wait_limit", "shflbw_spmm", "shflbw_conv2d",
+    "shflbw_layernorm_transpose", "shflbw_status_string", "shflbw_last_error",
 ]
 
 
@@ -60,6 +60,10 @@ def lib():
         L.shflbw_bind_device.argtypes = [vp, vp, vp]
         L.shflbw_set_tuning.restype = i32
         L.shflbw_set_tuning.argtypes = [vp, i32, i32]
+        L.shflbw_device_status.restype = i32
+        L.shflbw_device_status.argtypes = [vp, vp]
+        L.shflbw_set_wait_limit.restype = i32
+        L.shflbw_set_wait_limit.argtypes = [vp, i32]
         L.shflbw_spmm.restype = i32
         L.shflbw_spmm.argtypes = [vp, vp, i64, vp, i64, i64, i32, vp]
         L.shflbw_conv2d.restype = i32
@@ -172,6 +176,14 @@ class Matrix:
 
     def set_tuning(self, kernel=0, tile_n=0):
         _check(lib().shflbw_set_tuning(self._h, kernel, tile_n))
+
+    def set_wait_limit(self, tries):
+        _check(lib().shflbw_set_wait_limit(self._h, tries))
+
+    def device_status(self, stream=None):
+        """Waits for the stream; raises ShflbwError (status -10) if a bounded wait of
+        the slab kernel ran out in a launch on this matrix since the last call."""
+        _check(lib().shflbw_device_status(self._h, _stream_ptr(stream)))
 
     # -- device side
     def bind_device(self, device="cuda:0", stream=None):

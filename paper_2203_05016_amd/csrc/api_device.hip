@@ -40,6 +40,8 @@ int launch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long l
     a.A = view_of(A);
     a.table = reinterpret_cast<const uint32_t*>(static_cast<const char*>(A->dev_base) + A->off_table);
     a.first_chunk = reinterpret_cast<const int32_t*>(static_cast<const char*>(A->dev_base) + A->off_iter);
+    a.status = reinterpret_cast<int*>(static_cast<char*>(A->dev_base) + A->off_status);
+    a.spin_limit = A->wait_limit;
     a.X = static_cast<const _Float16*>(X);
     a.Y = Y;
     a.ldx = ldx; a.ldy = ldy; a.N = N;
@@ -256,10 +258,36 @@ int shflbw_bind_device(shflbw_matrix* A, void* dev_buf, void* stream)
         hipError_t e = hipMemcpyAsync(b + p.off, p.src, p.bytes, hipMemcpyHostToDevice, st);
         if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync");
     }
-    hipError_t e = hipStreamSynchronize(st);
+    hipError_t e = hipMemsetAsync(b + A->off_status, 0, 256, st);
+    if (e != hipSuccess) return hip_fail(e, "hipMemsetAsync");
+    e = hipStreamSynchronize(st);
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
     A->dev_base = dev_buf;
     return SHFLBW_OK;
+}
+
+int shflbw_device_status(shflbw_matrix* A, void* stream)
+{
+    using namespace shflbw;
+    if (!A) return fail(SHFLBW_ERR_NULL_ARG, "A is NULL");
+    int rc = check_bound(A);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* word = static_cast<char*>(A->dev_base) + A->off_status;
+    int seen = 0;
+    hipError_t e = hipMemcpyAsync(&seen, word, sizeof seen, hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync");
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    if (seen == 0) return SHFLBW_OK;
+    e = hipMemsetAsync(word, 0, sizeof seen, st);
+    if (e != hipSuccess) return hip_fail(e, "hipMemsetAsync");
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    return fail(SHFLBW_ERR_HANDOVER,
+                seen == 1 ? "a compute wavefront of the slab kernel gave up waiting for a chunk of X"
+                : seen == 2 ? "a loader wavefront of the slab kernel gave up waiting for a free stage"
+                            : "compute and loader wavefronts of the slab kernel gave up waiting");
 }
 
 int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int64_t ldy,

@@ -90,6 +90,7 @@ const char* shflbw_status_string(int status)
         case SHFLBW_ERR_HIP: return "HIP runtime error";
         case SHFLBW_ERR_NO_MEMORY: return "out of host memory";
         case SHFLBW_ERR_BAD_OPTION: return "bad tuning option";
+        case SHFLBW_ERR_HANDOVER: return "a bounded wait of a kernel ran out";
         default: return "unknown status";
     }
 }
@@ -295,8 +296,8 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
         A->off_cols = shflbw::align256(A->off_iter + sizeof(int32_t) * A->first_chunk.size());
         A->off_table = shflbw::align256(A->off_cols + sizeof(int32_t) * A->col_idx.size());
         A->off_vals = shflbw::align256(A->off_table + sizeof(uint32_t) * A->slab_table.size());
-        A->dev_bytes = shflbw::align256(A->off_vals + sizeof(uint16_t) * A->values.size());
-        if (A->dev_bytes == 0) A->dev_bytes = 256;
+        A->off_status = shflbw::align256(A->off_vals + sizeof(uint16_t) * A->values.size());
+        A->dev_bytes = A->off_status + 256;   // one word set by kernels whose bounded wait ran out
 
         guard.p = nullptr;
         *out = A;
@@ -376,6 +377,15 @@ int shflbw_set_tuning(shflbw_matrix* A, int kernel, int tile_n)
         return shflbw::fail(SHFLBW_ERR_BAD_OPTION, "tile_n must be 0, 64 or 128");
     A->tune_kernel = kernel;
     A->tune_tile_n = tile_n;
+    return SHFLBW_OK;
+}
+
+
+int shflbw_set_wait_limit(shflbw_matrix* A, int tries)
+{
+    if (!A) return shflbw::fail(SHFLBW_ERR_NULL_ARG, "A is NULL");
+    if (tries < 0) return shflbw::fail(SHFLBW_ERR_BAD_OPTION, "tries must be >= 0");
+    A->wait_limit = tries;
     return SHFLBW_OK;
 }
 

@@ -57,11 +57,12 @@ struct shflbw_matrix {
     std::vector<uint16_t> values;      // steps*V*TK binary16 bit patterns
 
     // device image (caller-owned buffer), byte offsets of the sections
-    size_t off_rows = 0, off_steps = 0, off_iter = 0, off_cols = 0, off_table = 0, off_vals = 0, dev_bytes = 0;
+    size_t off_rows = 0, off_steps = 0, off_iter = 0, off_cols = 0, off_table = 0, off_vals = 0, off_status = 0, dev_bytes = 0;
     void* dev_base = nullptr;
     int dev_id = -1;
 
     int tune_kernel = 0, tune_tile_n = 0;
+    int wait_limit = 1 << 20;          // polls per bounded wait of the slab kernel
     int dtype = 0;                     // SHFLBW_F16 or SHFLBW_BF16: format of the values and of the activations
 
     int total_steps() const { return step_ptr.empty() ? 0 : step_ptr.back(); }

@@ -26,8 +26,9 @@
 // step, a loader polls the latter only before it reuses a stage.  Wavefronts
 // therefore drift apart by up to two chunks, which is what overlaps one
 // wavefront's LDS latency with another's matrix-core time.  The polls are
-// bounded: a wavefront that does not see its condition within about a
-// million tries goes on regardless (wrong numbers instead of a hang).
+// bounded: a wavefront that does not see its condition within spin_limit
+// tries (about a million by default) goes on regardless - wrong numbers
+// instead of a hang - and sets a status word that the host can read back.
 //
 // Per step and lane the compressor stores one table word: the LDS byte
 // addresses of the lane's two transposed reads for the first instruction tile
@@ -65,7 +66,6 @@ constexpr int SLAB_IPL = SLAB_KC / 4 / SLAB_LOADERS;  // direct loads (4 rows ea
 static_assert(SLAB_IPL * SLAB_LOADERS * 4 == SLAB_KC, "chunk must divide evenly");
 static_assert(SLAB_IPL * (SLAB_LEAD - 1) < 16, "vmcnt immediates below use the low four bits only");
 
-constexpr int SLAB_SPIN_LIMIT = 1 << 20;
 constexpr int SLAB_BUFFER_FLAGS = 0x00020000;     // last word of a raw buffer descriptor: untyped 32-bit data
 
 typedef __attribute__((address_space(3))) char* lds_char_ptr;
@@ -89,6 +89,8 @@ struct SlabArgs {
     long ldx, ldy, N;
     int K, C;
     int n_tiles, gblocks;     // 128-column tiles, blocks of GW groups
+    int spin_limit;           // polls per bounded wait
+    int* status;              // set to non-zero by a wavefront whose wait ran out
 };
 
 template <int V, int GW, typename OutT, bool BF>
@@ -138,6 +140,10 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
         return __builtin_amdgcn_ballot_w64(lane < count && v < need) == 0;
     };
     static_assert(GW <= 16 && SLAB_LOADERS + 16 + 16 <= 32 + 4, "flag reads stay inside the flag block");
+    // a wait that ran out is recorded for the host (the wavefront goes on: wrong numbers, no hang)
+    auto give_up = [&](int who) __attribute__((always_inline)) {
+        if (lane == 0) atomicOr(a.status, who);
+    };
 
     if (wave >= GW) {
         // ------------------------------------------------------------ loader
@@ -185,9 +191,12 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
             if (j < C) {
                 // chunk j takes the stage of chunk j-STAGES, whose last readers run
                 // in iteration j-LEAD-1 = c-1
-                if (j >= SLAB_STAGES)
-                    for (int tries = 0; !reached(progress, GW, c) && tries < SLAB_SPIN_LIMIT; ++tries)
+                if (j >= SLAB_STAGES) {
+                    int tries = 0;
+                    for (; !reached(progress, GW, c) && tries < a.spin_limit; ++tries)
                         __builtin_amdgcn_s_sleep(1);
+                    if (tries >= a.spin_limit && !reached(progress, GW, c)) give_up(2);
+                }
                 asm volatile("" ::: "memory");
                 issue_chunk(j);
             }
@@ -282,8 +291,9 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
             }
             if (seen < e + 1) {
                 // the flags are read only when the chunk is not already known to be in
+                int tries = 0;
 #pragma nounroll
-                for (int tries = 0; tries < SLAB_SPIN_LIMIT; ++tries) {
+                for (;; ++tries) {
                     const int v = landed[lane & (SLAB_LOADERS - 1)];
                     int m = __builtin_amdgcn_readlane(v, 0);
 #pragma unroll
@@ -293,6 +303,10 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
                     }
                     seen = m;
                     if (m >= e + 1) break;
+                    if (tries >= a.spin_limit) {
+                        give_up(1);
+                        break;
+                    }
                     __builtin_amdgcn_s_sleep(1);
                 }
             }

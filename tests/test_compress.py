@@ -167,6 +167,9 @@ def test_device_calls_validate_before_touching_the_gpu():
     assert L.shflbw_bind_device(A._h, ctypes.c_void_p(8), None) == -2           # misaligned
     assert L.shflbw_set_tuning(A._h, 5, 0) == -9 and L.shflbw_set_tuning(A._h, 0, 100) == -9
     assert L.shflbw_set_tuning(A._h, 1, 64) == 0
+    assert L.shflbw_device_status(None, None) == -1 and L.shflbw_device_status(A._h, None) == -6
+    assert L.shflbw_set_wait_limit(A._h, -1) == -9 and L.shflbw_set_wait_limit(A._h, 1000) == 0
+    assert binding.lib().shflbw_status_string(-10) == b"a bounded wait of a kernel ran out"
 
 
 def test_bfloat16_weights_round_trip_bitwise():

@@ -105,3 +105,31 @@ def test_slab_distant_steps_are_bridged():
         Y = run_spmm(p, kernel=SLAB, out_dtype=out_dtype)
         Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
         assert_within_scaled_tolerance(Y, Yr, S, what="slab distant steps")
+
+
+def test_slab_reports_a_wait_that_ran_out():
+    """The hand-over between loader and compute wavefronts is bounded; with the
+    bound at zero every wait gives up at once (the kernel still ends normally,
+    its numbers are not to be trusted) and the status call says so, once."""
+    import torch
+    announce("slab wait limit")
+    p = synth.make_spmm(16 * 32, 1024, 1024, 32, 0.5, seed=161)
+    A = binding.compress(p.W, p.mask, p.perm, 32).bind_device("cuda:0")
+    A.set_tuning(SLAB, 0)
+    X = torch.from_numpy(p.X).to("cuda:0")
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    Y = A.spmm(X)
+    A.device_status()                      # nothing ran out
+    assert_within_scaled_tolerance(Y.cpu().numpy(), Yr, S, what="before")
+    A.set_wait_limit(0)
+    A.spmm(X)
+    with pytest.raises(binding.ShflbwError) as e:
+        A.device_status()
+    assert e.value.status == -10
+    A.device_status()                      # the word was cleared
+    A.set_wait_limit(1 << 20)
+    Y = A.spmm(X)
+    A.device_status()
+    assert_within_scaled_tolerance(Y.cpu().numpy(), Yr, S, what="after")
+    with pytest.raises(binding.ShflbwError):
+        A.set_wait_limit(-1)
