@@ -104,6 +104,7 @@ def measure_spmm(p, steps, warmup, cold=True, **kw):
     rot = rotation_for(p) if cold else 1
     c = Case(p, rot, **kw)
     ms = time_steps(c.step, steps, warmup)
+    c.A.device_status()   # raises if a bounded hand-over wait ran out in any of these launches
     r = dict(ms=ms, tflops=c.flop() / (ms * 1e-3) / 1e12, gbps=c.bytes() / (ms * 1e-3) / 1e9,
              nnz=c.info["nnz"], sparsity=c.info["sparsity"], bytes=c.bytes(), flop=c.flop(),
              rotate=rot)
