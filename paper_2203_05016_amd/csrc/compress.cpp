@@ -259,32 +259,29 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
         }
 
         if (A->slab_ok) {
-            // What each lane of the slab kernel needs to run a step (see slab_kernel.hip):
-            // the LDS byte addresses of its two transposed reads for the first
-            // instruction tile, and how many chunks the step lies past the one before.
-            A->slab_table.resize(steps * 64);
+            // What the slab kernel needs to run a step (see slab_kernel.hip): per pair of
+            // slots (j, j+4) that one lane reads, the LDS offsets (in 16-byte units, row
+            // swizzle included) of the two rows, and how many chunks the step lies past
+            // the one before.  Word w of a step serves slots j = 8*(w/4) + w%4 and j+4.
+            const int WPS = TK / 2;
+            A->slab_table.resize(steps * WPS);
             A->first_chunk.assign(G, 0);
-            const bool small = (V == 16);
             for (int g = 0; g < G; ++g) {
                 int prev = 0;
                 for (size_t st = (size_t)A->step_ptr[g]; st < (size_t)A->step_ptr[g + 1]; ++st) {
                     if (st == (size_t)A->step_ptr[g]) prev = A->first_chunk[g] = A->step_iter[st];
                     const uint32_t d = (uint32_t)(A->step_iter[st] - prev);   // 0 .. SLAB_MAX_CHUNK_STEP
                     prev = A->step_iter[st];
-                    for (int lane = 0; lane < 64; ++lane) {
-                        const int bl = lane >> 4, il = lane & 15;
-                        const int kq = small ? (8 * bl + (il >> 2)) : (8 * (bl >> 1) + (il >> 2));
-                        const int qc = small ? ((il & 3) >> 1) : (2 * (bl & 1) + ((il & 3) >> 1));
-                        const int qbyte = (il & 1) << 3;
-                        uint32_t word = (d & 7u) | ((d >> 3) << 31);
+                    for (int w = 0; w < WPS; ++w) {
+                        const int j = 8 * (w >> 2) + (w & 3);
+                        uint32_t word = d << 26;
                         for (int h = 0; h < 2; ++h) {
-                            const int k = A->col_idx[st * TK + kq + 4 * h];
+                            const int k = A->col_idx[st * TK + j + 4 * h];
                             const int row = k < 0 ? shflbw::SLAB_ZERO_ROW : k % shflbw::SLAB_RING_ROWS;
-                            const uint32_t addr = (uint32_t)(row * shflbw::SLAB_ROW_BYTES + qbyte +
-                                                             ((qc ^ shflbw::slab_swizzle(row)) << 4));
-                            word |= (addr >> 3) << (h ? 17 : 3);
+                            const uint32_t field = (uint32_t)(row * (shflbw::SLAB_ROW_BYTES / 16) + shflbw::slab_swizzle(row));
+                            word |= field << (13 * h);
                         }
-                        A->slab_table[st * 64 + lane] = word;
+                        A->slab_table[st * WPS + w] = word;
                     }
                 }
             }

@@ -25,16 +25,16 @@
 // chunk finds all rows of a step resident at once; a step whose columns
 // would reach one chunk more is cut short and padded, and every group's step
 // count is rounded up to a multiple of SLAB_UNROLL with empty steps.
-// slab_table holds, per step and lane, what the slab kernel needs to run the
-// step: bits 3-16 and 17-30 are the LDS byte addresses, divided by 8, of the
-// lane's two transposed reads for the first instruction tile (row of the ring
-// = column mod SLAB_RING_ROWS, or SLAB_ZERO_ROW for padding; the swizzled
-// 16-byte slot inside the row that the lane's position in the operand asks
-// for); bits 0-2 and 31 hold, as a 4-bit number, how many chunks the step's
-// last column lies past that of the group's previous step (the step may run
-// once that chunk is resident).  first_chunk holds the chunk of each group's
-// first step.  Steps more than SLAB_MAX_CHUNK_STEP chunks apart are bridged by
-// empty steps.
+// slab_table holds what the slab kernel needs to run a step: T_K/2 words per
+// step, word w for the slot pair (j, j+4), j = 8*(w/4) + w%4, that one lane's
+// two transposed reads cover.  Bits 0-12 and 13-25: the LDS offsets, in
+// 16-byte units, of the two slots' rows (row of the ring = column mod
+// SLAB_RING_ROWS, or SLAB_ZERO_ROW for padding) with the row's swizzle in the
+// low four bits - a lane gets its read address by an exclusive-or with its own
+// position in the operand; bits 26-29: how many chunks the step's last column
+// lies past that of the group's previous step (the step may run once that
+// chunk is resident).  first_chunk holds the chunk of each group's first step.
+// Steps more than SLAB_MAX_CHUNK_STEP chunks apart are bridged by empty steps.
 //
 // values: for each k-step, for each 32-row block rb of the group (one block
 // when V = 16), 64 lanes x 8 binary16 in the operand order of the
@@ -52,7 +52,7 @@ struct shflbw_matrix {
     bool slab_ok = false;              // windowed layout in use
     int slab_chunks = 0;               // C = ceil(K / SLAB_KC)
     std::vector<int32_t> step_iter;    // steps, only when slab_ok: chunk of each step's last column
-    std::vector<uint32_t> slab_table;  // steps*64, only when slab_ok (see above)
+    std::vector<uint32_t> slab_table;  // steps*TK/2, only when slab_ok (see above)
     std::vector<int32_t> first_chunk;  // G, only when slab_ok: chunk of each group's first step
     std::vector<uint16_t> values;      // steps*V*TK binary16 bit patterns
 
@@ -83,7 +83,7 @@ constexpr int SLAB_UNROLL = 4;                                      // steps per
 constexpr int SLAB_TN = 128;                                        // output columns per workgroup of the slab kernel
 constexpr int SLAB_ROW_BYTES = SLAB_TN * 2;                         // one staged row of X in LDS
 constexpr int SLAB_MAX_CHUNK_STEP = 15;                             // largest chunk difference a table word can hold
-static_assert((SLAB_ZERO_ROW + 1) * SLAB_ROW_BYTES / 8 <= (1 << 14), "LDS addresses are stored in 14 bits, in units of 8 bytes");
+static_assert((SLAB_ZERO_ROW + 1) * SLAB_ROW_BYTES / 16 <= (1 << 13), "LDS offsets are stored in 13 bits, in units of 16 bytes");
 // Swizzle of the 16-byte slots inside a staged row of X (the loader stores logical slot q of
 // ring row r at slot q ^ slab_swizzle(r); the table's read addresses include it).  One
 // transposed read covers, per 32 lanes, four rows of a step and a 64-byte window (four slots,

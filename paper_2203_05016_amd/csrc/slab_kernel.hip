@@ -30,14 +30,16 @@
 // tries (about a million by default) goes on regardless - wrong numbers
 // instead of a hang - and sets a status word that the host can read back.
 //
-// Per step and lane the compressor stores one table word: the LDS byte
-// addresses of the lane's two transposed reads for the first instruction tile
-// (ring row = column mod 384, swizzled slot included; the other tiles differ
-// from it in the tile's bits only, one exclusive-or each), and by how many
-// chunks the step lies past the one before it.  Nothing but two masks is left
-// to compute per step: the loop is bound by instruction issue (address
-// arithmetic and matrix instructions share the vector issue port), not by the
-// traffic.
+// Per step the compressor stores 8 table words (16 for V = 16), one per pair
+// of rows that a lane's two transposed reads take: the rows' LDS offsets with
+// the swizzle folded in, and by how many chunks the step lies past the one
+// before it.  A lane loads the word of its pair (the 64 lanes of a wavefront
+// read 32 or 64 bytes in all) and gets its read addresses by an exclusive-or
+// with a per-lane constant that holds its position in the operand and the
+// instruction tile: two shifts and eight fused mask-and-xor per step.  The
+// loop is bound by instruction issue (address arithmetic and matrix
+// instructions share the vector issue port) and by bytes from the L2, which is
+// why the table is small and pre-digested.
 //
 // Algorithm 1's parts: BulkLoadMeta = each step's weight tile and table word
 // fetched into registers four steps ahead (two for V = 64, whose two row
@@ -82,7 +84,7 @@ __device__ __forceinline__ void meta_dma16(const void* g, unsigned lds_off)
 }
 struct SlabArgs {
     PackedView A;
-    const uint32_t* table;    // steps*64 table words (LDS addresses of the lane's reads, chunk difference)
+    const uint32_t* table;    // steps*TK/2 table words (LDS offsets of row pairs, chunk difference)
     const int32_t* first_chunk;  // chunk of each group's first step
     const _Float16* X;
     void* Y;
@@ -250,12 +252,18 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     // scalar register and the lane's in one vector register, so a load costs no vector
     // arithmetic.  Offsets beyond the group's steps would read as zero.
     typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+    constexpr int WPS = TK / 2;                       // table words per step
     const __amdgpu_buffer_rsrc_t tab_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint32_t*>(a.table + (long)sbeg * 64), 0, nsteps * 256, SLAB_BUFFER_FLAGS);
+        const_cast<uint32_t*>(a.table + (long)sbeg * WPS), 0, nsteps * WPS * 4, SLAB_BUFFER_FLAGS);
+    // this lane's pair of rows and its position inside them (see the transposed read's lane map)
+    const int bl = lane >> 4, il = lane & 15;
+    const int pair = SMALL ? 4 * bl + (il >> 2) : 4 * (bl >> 1) + (il >> 2);
+    const int qc = SMALL ? ((il & 3) >> 1) : (2 * (bl & 1) + ((il & 3) >> 1));
+    const unsigned lane_bits = (unsigned)(qc << 4) | (unsigned)((il & 1) << 3);
     const __amdgpu_buffer_rsrc_t val_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<half8*>(a.A.values + (long)sbeg * RB * 64), 0, nsteps * RB * 1024, SLAB_BUFFER_FLAGS);
     auto load_table = [&](int s) __attribute__((always_inline)) {
-        return __builtin_amdgcn_raw_buffer_load_b32(tab_rsrc, lane * 4, s * 256, 0);
+        return __builtin_amdgcn_raw_buffer_load_b32(tab_rsrc, pair * 4, s * (WPS * 4), 0);
     };
     auto load_weights = [&](int s, int rb) __attribute__((always_inline)) {
         return __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, lane * 16,
@@ -281,7 +289,7 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
         for (int u = 0; u < PD; ++u) {
             const unsigned tab = mt[u];
             const unsigned head = __builtin_amdgcn_readfirstlane(tab);
-            chunk += (head & 7) | ((head >> 31) << 3);
+            chunk += (head >> 26) & 15;
             const int e = chunk;
             if (e != cur) {
                 // this wavefront's reads of chunks below e - WINDOW + 1 are over
@@ -312,15 +320,16 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
             }
             asm volatile("" ::: "memory");
 
-            const unsigned addr0 = tab & 0x1fff8u, addr1 = (tab >> 14) & 0x1fff8u;
+            const unsigned row0 = tab << 4, row1 = tab >> 9;   // the offsets sit in bits 4-16 of these
             // all transposed reads of the step go out before the first product
             half8 x[NT];
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 // tile t: 16-byte slot (SMALL ? 2t : 4t) further on, before the swizzle
                 constexpr int TILE_BITS = SMALL ? 32 : 64;
-                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(smem + (addr0 ^ (t * TILE_BITS))));
-                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(smem + (addr1 ^ (t * TILE_BITS))));
+                const unsigned pos = lane_bits ^ (unsigned)(t * TILE_BITS);
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(smem + ((row0 & 0x1fff0u) ^ pos)));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(smem + ((row1 & 0x1fff0u) ^ pos)));
                 half4 l4 = __builtin_bit_cast(half4, lo), h4 = __builtin_bit_cast(half4, hi);
                 x[t] = half8{l4[0], l4[1], l4[2], l4[3], h4[0], h4[1], h4[2], h4[3]};
             }
