@@ -27,10 +27,10 @@ sys.path.insert(0, ROOT)
 
 MFMA_F16_PEAK = 2.5166e15      # 256 CU x 4096 FLOP/clk x 2.4 GHz
 HBM_PEAK = 8.0e12
-L2_TO_CU_BYTES = 359.9e6        # 2.812e6 read requests of 128 B per launch of the headline kernel
+L2_TO_CU_BYTES = 334.0e6        # 2.609e6 read requests of 128 B per launch of the headline kernel
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by the same counters on a 64 MiB copy (profiles/slab_kernel_ffn_config2_pmc.md)
-MEASURED_TRAFFIC_BYTES = 121.7e6
+MEASURED_TRAFFIC_BYTES = 109.2e6
 PAPER_CONTEXT = "paper: up to 1.81x/4.18x/1.90x over cuBLAS dense at 75% on V100/T4/A100 (context only)"
 
 
