@@ -18,15 +18,17 @@
 // normalised in fp32, written transposed into an LDS tile and stored as 64
 // rows of 128 bytes.  It is bound by HBM: 2*N*K bytes read and 2*N*K written.
 //
-// When a block of 64 (or 32) tokens with all its features fits the LDS, a
+// When a block of 32 (or 64) tokens with all its features fits the LDS, a
 // second kernel keeps it there instead: every activation is read from HBM
-// once, the statistics come from the same loads, and the transposed rows are
-// gathered from LDS columns (row pitch chosen so that the 8 token rows a
-// lane reads fall into different banks).
+// once, the statistics come from the same loads (four tokens per wavefront),
+// and the transposed rows are gathered from LDS columns, two neighbouring
+// features per lane (row pitch chosen so that the 64 four-byte reads of a
+// wavefront fall into 64 different banks).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
 #include <string>
+#include <type_traits>
 
 #include "shflbw.h"
 #include "shflbw_internal.h"
@@ -209,9 +211,28 @@ __global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_kernel(LnAr
 }
 
 // ---------------------------------------------------------------- LDS-resident variant
-// TOK tokens x K features (pitch P halves, P/2 = 1 mod 64) + statistics + gamma/beta in fp32.
-template <bool BF, int TOK>
-__global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_resident_kernel(LnArgs a, int P)
+// TOK tokens x K features (pitch P halves) + statistics + gamma/beta in fp32.  A lane of
+// the store phase takes two neighbouring features of 8 tokens: 8 four-byte LDS reads
+// for two 16-byte stores.  The 64 lanes of a wavefront read, per token, 64/CH feature
+// pairs for each of CH token chunks; with P/2 = 64/CH/8 (mod 8) the chunks' rows start
+// 64/CH banks apart, so the 64 words fall into 64 different banks.
+// lo = low half of w + c, hi = high half of w + c, in fp32.  For float16 the widening
+// rides on the mixed-precision multiply-add (x * 1 + c, rounded once: the same bits as
+// a conversion followed by an addition), which halves the instructions.
+template <bool BF>
+__device__ __forceinline__ void ln_add_pair(unsigned w, float c, float& lo, float& hi)
+{
+    if constexpr (BF) {
+        lo = __builtin_bit_cast(float, w << 16) + c;
+        hi = __builtin_bit_cast(float, w & 0xffff0000u) + c;
+    } else {
+        asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel_hi:[1,0,0]" : "=v"(lo) : "v"(w), "v"(c));
+        asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(hi) : "v"(w), "v"(c));
+    }
+}
+
+template <bool BF, int TOK, bool NORM>
+__global__ __launch_bounds__(16 * TOK) void layernorm_transpose_resident_kernel(LnArgs a, int P)
 {
     extern __shared__ __attribute__((aligned(16))) char ln_smem[];
     uint16_t* xs = reinterpret_cast<uint16_t*>(ln_smem);                       // [TOK][P]
@@ -219,25 +240,32 @@ __global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_resident_ke
     float* st_rstd = st_mean + TOK;                                             // [TOK]
     float* gam = st_rstd + TOK;                                                 // [K]
     float* bet = gam + a.K;                                                     // [K]
-    constexpr int TPW = TOK / LN_WAVES;   // tokens per wavefront
+    constexpr int WAVES = TOK / 4;        // 8 or 16 wavefronts
+    constexpr int TPW = 4;                // tokens per wavefront
     constexpr int CH = TOK / 8;           // 16-byte token chunks per output row
-    constexpr int FW = 64 / CH;           // features one wavefront stores per pass
+    constexpr int FP = 64 / CH;           // feature pairs one wavefront stores per pass
+    constexpr bool WIDE = (TOK == 32);    // its pitch keeps every row 8-byte aligned
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const long n0 = (long)blockIdx.x * TOK;
     const int K = a.K;
 
-    for (int k = tid; k < K; k += 64 * LN_WAVES) {
-        gam[k] = (a.normalize && a.gamma) ? ln_widen<BF>(a.gamma[k]) : 1.f;
-        bet[k] = (a.normalize && a.beta) ? ln_widen<BF>(a.beta[k]) : 0.f;
+    if (NORM) {
+        for (int k = tid; k < K; k += 64 * WAVES) {
+            gam[k] = a.gamma ? ln_widen<BF>(a.gamma[k]) : 1.f;
+            bet[k] = a.beta ? ln_widen<BF>(a.beta[k]) : 0.f;
+        }
     }
 
     // ---- load the block once: LDS copy and, from the same registers, the statistics
     float s1[TPW], s2[TPW], pivot[TPW];
 #pragma unroll
     for (int t = 0; t < TPW; ++t) { s1[t] = 0.f; s2[t] = 0.f; pivot[t] = 0.f; }
-    for (int kc0 = 0; kc0 < K; kc0 += 2 * 64 * 8) {
+    const bool all_tokens = n0 + TOK <= a.N;
+    // one sweep of 1024 features; FULL = every token and feature of it exists
+    auto sweep = [&](int kc0, auto full_tag) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full_tag)::value;
         ln_ushort8 v[TPW][2];
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
@@ -245,11 +273,15 @@ __global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_resident_ke
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const int kc = kc0 + h * 512 + lane * 8;
-                v[t][h] = ln_ushort8{0, 0, 0, 0, 0, 0, 0, 0};
-                if (n < a.N && kc < K) v[t][h] = *reinterpret_cast<const ln_ushort8*>(a.x + n * a.ldx + kc);
+                if (FULL) {
+                    v[t][h] = *reinterpret_cast<const ln_ushort8*>(a.x + n * a.ldx + kc);
+                } else {
+                    v[t][h] = ln_ushort8{0, 0, 0, 0, 0, 0, 0, 0};
+                    if (n < a.N && kc < K) v[t][h] = *reinterpret_cast<const ln_ushort8*>(a.x + n * a.ldx + kc);
+                }
             }
         }
-        if (kc0 == 0) {
+        if (NORM && kc0 == 0) {
 #pragma unroll
             for (int t = 0; t < TPW; ++t)
                 pivot[t] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
@@ -260,22 +292,41 @@ __global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_resident_ke
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const int kc = kc0 + h * 512 + lane * 8;
-                if (kc < K) {
-                    unsigned* dst = reinterpret_cast<unsigned*>(xs + (wave * TPW + t) * P + kc);   // 4-byte aligned
+                if (FULL || kc < K) {
+                    unsigned w[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        dst[e] = (unsigned)v[t][h][2 * e] | ((unsigned)v[t][h][2 * e + 1] << 16);
+                        w[e] = (unsigned)v[t][h][2 * e] | ((unsigned)v[t][h][2 * e + 1] << 16);
+                    uint16_t* row = xs + (wave * TPW + t) * P + kc;
+                    if (WIDE) {
+                        uint2* dst = reinterpret_cast<uint2*>(row);
+                        dst[0] = uint2{w[0], w[1]};
+                        dst[1] = uint2{w[2], w[3]};
+                    } else {
+                        unsigned* dst = reinterpret_cast<unsigned*>(row);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float d = ln_widen<BF>(v[t][h][e]) - pivot[t];
-                        s1[t] += d;
-                        s2[t] += d * d;
+                        for (int e = 0; e < 4; ++e) dst[e] = w[e];
+                    }
+                    if (NORM) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float d0, d1;
+                            ln_add_pair<BF>(w[e], -pivot[t], d0, d1);
+                            s1[t] += d0;
+                            s2[t] += d0 * d0;
+                            s1[t] += d1;
+                            s2[t] += d1 * d1;
+                        }
                     }
                 }
             }
         }
+    };
+    for (int kc0 = 0; kc0 < K; kc0 += 2 * 64 * 8) {
+        if (all_tokens && kc0 + 2 * 64 * 8 <= K) sweep(kc0, std::true_type{});
+        else sweep(kc0, std::false_type{});
     }
-    if (a.normalize) {
+    if (NORM) {
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
 #pragma unroll
@@ -284,37 +335,60 @@ __global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_resident_ke
                 s2[t] += __shfl_xor(s2[t], off, 64);
             }
         }
-    }
-    if (lane == 0) {
+        if (lane == 0) {
 #pragma unroll
-        for (int t = 0; t < TPW; ++t) {
-            const float m = s1[t] / (float)K;
-            float var = s2[t] / (float)K - m * m;
-            var = var > 0.f ? var : 0.f;
-            st_mean[wave * TPW + t] = a.normalize ? pivot[t] + m : 0.f;
-            st_rstd[wave * TPW + t] = a.normalize ? 1.0f / __builtin_sqrtf(var + a.eps) : 1.f;
+            for (int t = 0; t < TPW; ++t) {
+                const float m = s1[t] / (float)K;
+                float var = s2[t] / (float)K - m * m;
+                var = var > 0.f ? var : 0.f;
+                st_mean[wave * TPW + t] = pivot[t] + m;
+                st_rstd[wave * TPW + t] = 1.0f / __builtin_sqrtf(var + a.eps);
+            }
         }
     }
     __syncthreads();
 
-    // ---- transposed rows: a wavefront stores FW feature rows x TOK tokens per pass;
-    // lane -> feature lane/CH of the pass, tokens (lane%CH)*8 .. +7
-    const int kk = lane / CH, tchunk = lane % CH;
+    // ---- transposed rows: a wavefront stores 2*FP feature rows x TOK tokens per pass;
+    // lane -> features 2*(lane/CH), +1 of the pass, tokens (lane%CH)*8 .. +7
+    const int kk2 = lane / CH, tchunk = lane % CH;
     float mean[8], rstd[8];
+    if (NORM) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { mean[e] = st_mean[tchunk * 8 + e]; rstd[e] = st_rstd[tchunk * 8 + e]; }
+        for (int e = 0; e < 8; ++e) { mean[e] = st_mean[tchunk * 8 + e]; rstd[e] = st_rstd[tchunk * 8 + e]; }
+    }
     const long n = n0 + tchunk * 8;
-    for (int kb = wave * FW; kb < K; kb += LN_WAVES * FW) {
-        const int k = kb + kk;
-        if (k < K && n < a.N) {
-            const float g = gam[k], b = bet[k];
-            ln_ushort8 o;
+    const unsigned* xw = reinterpret_cast<const unsigned*>(xs) + tchunk * 8 * (P / 2);
+    const int Q = P / 2;
+    if (n < a.N) {
+#pragma unroll 2
+        for (int kb = wave * 2 * FP; kb < K; kb += WAVES * 2 * FP) {
+            const int k = kb + 2 * kk2;      // K is even: the pair exists or does not
+            if (k < K) {
+                unsigned w[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint16_t raw = xs[(tchunk * 8 + e) * P + k];
-                o[e] = a.normalize ? ln_narrow<BF>((ln_widen<BF>(raw) - mean[e]) * rstd[e] * g + b) : raw;
+                for (int e = 0; e < 8; ++e) w[e] = xw[e * Q + (k >> 1)];
+                ln_ushort8 o0, o1;
+                if (NORM) {
+                    const float2 g = *reinterpret_cast<const float2*>(gam + k);
+                    const float2 b = *reinterpret_cast<const float2*>(bet + k);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        float lo, hi;
+                        ln_add_pair<BF>(w[e], -mean[e], lo, hi);
+                        o0[e] = ln_narrow<BF>(lo * rstd[e] * g.x + b.x);
+                        o1[e] = ln_narrow<BF>(hi * rstd[e] * g.y + b.y);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        o0[e] = (uint16_t)(w[e] & 0xffffu);
+                        o1[e] = (uint16_t)(w[e] >> 16);
+                    }
+                }
+                uint16_t* dst = a.out + (long)k * a.ldo + n;
+                __builtin_nontemporal_store(o0, reinterpret_cast<ln_ushort8*>(dst));
+                __builtin_nontemporal_store(o1, reinterpret_cast<ln_ushort8*>(dst + a.ldo));
             }
-            __builtin_nontemporal_store(o, reinterpret_cast<ln_ushort8*>(a.out + (long)k * a.ldo + n));
         }
     }
 }
@@ -350,47 +424,47 @@ extern "C" int shflbw_layernorm_transpose(const void* x, int64_t ldx, const void
     a.ldx = (long)ldx; a.ldo = (long)ldo; a.N = (long)N; a.K = K; a.eps = eps;
     a.normalize = normalize ? 1 : 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // LDS-resident variant when a block of tokens with all its features fits: 64 tokens per
-    // workgroup, or 32 when that fills the chip better or is all that fits
+    // LDS-resident variant when a block of tokens with all its features fits
     auto resident_bytes = [&](int tok, int& pitch) {
-        int pad = 2;
-        while (((K + pad) / 2) % 64 != 1) pad += 2;     // 8 rows apart -> 8 banks apart
+        const int want = tok == 32 ? 2 : 1;             // (pitch / 2) mod 8, see the kernel
+        int pad = 0;
+        while (((K + pad) / 2) % 8 != want) pad += 2;
         pitch = K + pad;
         return (size_t)tok * pitch * 2 + 2 * (size_t)tok * 4 + 2 * (size_t)K * 4;
     };
     const size_t lds_cap = 160 * 1024 - 256;
     int pitch = 0;
     int tok = 0;
-    if (resident_bytes(64, pitch) <= lds_cap && (N + 63) / 64 >= 256) tok = 64;
+    // Blocks of 32 tokens (64-byte row segments, two workgroups per CU) are faster while input
+    // and output together stay well inside the 256 MB memory-side cache, where the halves of a
+    // line still meet; beyond that the 128-byte segments of 64-token blocks win (measured:
+    // 26 against 27 us at 134 MB, 53 against 44 us at 201 MB).
+    const bool big = 4.0 * (double)N * (double)K > 160e6;
+    if (big && resident_bytes(64, pitch) <= lds_cap) tok = 64;
     else if (resident_bytes(32, pitch) <= lds_cap) tok = 32;
     if (tok) {
         const size_t bytes = resident_bytes(tok, pitch);
         const int64_t rwgs = (N + tok - 1) / tok;
         if (rwgs > 0x7fffffffLL) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
-        const void* fn = dtype == SHFLBW_BF16
-            ? (tok == 64 ? (const void*)&layernorm_transpose_resident_kernel<true, 64>
-                         : (const void*)&layernorm_transpose_resident_kernel<true, 32>)
-            : (tok == 64 ? (const void*)&layernorm_transpose_resident_kernel<false, 64>
-                         : (const void*)&layernorm_transpose_resident_kernel<false, 32>);
+        typedef void (*resident_fn)(LnArgs, int);
+        static const resident_fn table[8] = {
+            &layernorm_transpose_resident_kernel<false, 32, false>, &layernorm_transpose_resident_kernel<false, 32, true>,
+            &layernorm_transpose_resident_kernel<false, 64, false>, &layernorm_transpose_resident_kernel<false, 64, true>,
+            &layernorm_transpose_resident_kernel<true, 32, false>,  &layernorm_transpose_resident_kernel<true, 32, true>,
+            &layernorm_transpose_resident_kernel<true, 64, false>,  &layernorm_transpose_resident_kernel<true, 64, true>};
+        const int which = (dtype == SHFLBW_BF16 ? 4 : 0) + (tok == 64 ? 2 : 0) + (a.normalize ? 1 : 0);
+        const resident_fn fn = table[which];
         // the attribute is raised once per kernel and device
-        static thread_local int raised_on[4] = {-1, -1, -1, -1};
-        const int which = (dtype == SHFLBW_BF16 ? 2 : 0) + (tok == 64 ? 1 : 0);
+        static thread_local int raised_on[8] = {-1, -1, -1, -1, -1, -1, -1, -1};
         int dev = 0;
         hipError_t ea = hipGetDevice(&dev);
         if (ea != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(ea));
         if (raised_on[which] != dev) {
-            ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            ea = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             if (ea != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(ea));
             raised_on[which] = dev;
         }
-        const dim3 grid((unsigned)rwgs), block(64 * LN_WAVES);
-        if (dtype == SHFLBW_BF16) {
-            if (tok == 64) hipLaunchKernelGGL((layernorm_transpose_resident_kernel<true, 64>), grid, block, bytes, st, a, pitch);
-            else hipLaunchKernelGGL((layernorm_transpose_resident_kernel<true, 32>), grid, block, bytes, st, a, pitch);
-        } else {
-            if (tok == 64) hipLaunchKernelGGL((layernorm_transpose_resident_kernel<false, 64>), grid, block, bytes, st, a, pitch);
-            else hipLaunchKernelGGL((layernorm_transpose_resident_kernel<false, 32>), grid, block, bytes, st, a, pitch);
-        }
+        hipLaunchKernelGGL(fn, dim3((unsigned)rwgs), dim3(16 * tok), bytes, st, a, pitch);
         hipError_t el = hipGetLastError();
         if (el != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(el));
         return SHFLBW_OK;
