@@ -124,16 +124,20 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     };
     int cols0[BULK_LOADS];
     load_cols(0, cols0);   // in flight while the input box is staged
-    // so are the weight operands of the first CONV_PD steps
-    const half8* valp = a.A.values + (long)sbeg * RB * 64 + lane;
-    const int last = nsteps - 1;
+    // so are the weight operands of the first CONV_PD steps.  Buffer loads: the descriptor
+    // covers this group's steps, a step beyond them reads as zero, so no load is conditional
+    const __amdgpu_buffer_rsrc_t val_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<half8*>(a.A.values + (long)sbeg * RB * 64), 0, nsteps * RB * 1024, GATHER_BUFFER_FLAGS);
+    auto load_w = [&](int s, int rb) __attribute__((always_inline)) {
+        return __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, lane * 16,
+                                                                                (s * RB + rb) * 1024, 0));
+    };
     half8 w[CONV_PD][RB];
 #pragma unroll
     for (int u = 0; u < CONV_PD; ++u) {
-        const int sn = u < nsteps ? u : last;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-            w[u][rb] = nsteps > 0 ? valp[((long)sn * RB + rb) * 64] : half8{0, 0, 0, 0, 0, 0, 0, 0};
+        for (int rb = 0; rb < RB; ++rb) w[u][rb] = load_w(u, rb);
+        __builtin_amdgcn_sched_barrier(0);   // sets in issue order: the loop's wait counts assume set 0 is the oldest
     }
 
     // ---- stage the input box: element (c, iy, ix, bb) at xin[c*plane + (iy*cols_in + ix)*tb + bb]
@@ -197,45 +201,51 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
         typedef unsigned short ushort8 __attribute__((ext_vector_type(8)));
         const ushort8* kl = reinterpret_cast<const ushort8*>(klist) + khalf;   // 8 slots of this lane's half
 
-        // StitchTile of one step: 8 reduction indices x up to NT positions per lane
-        auto gather = [&](int s, half8 (&x)[NT]) __attribute__((always_inline)) {
-            const ushort8 ko = kl[(s & (CONV_BULK - 1)) * 2];
+        // StitchTile of one step: 8 reduction indices x up to NT positions per lane.  The
+        // list entry of a step is read one step before its gathers go out, the gathers one
+        // step before their product, so a step waits for one LDS round trip at most.  The
+        // loop is straight-line code over whole batches of CONV_PD steps: a step past the
+        // group's last one multiplies zero weights (the descriptor's range) with the zero
+        // plane (the list's filler), and every load is unconditional, which keeps the
+        // register sets static and the wait counts exact.
+        auto read_list = [&](int s) __attribute__((always_inline)) { return kl[(s & (CONV_BULK - 1)) * 2]; };
+        auto gather = [&](const ushort8& ko, half8 (&x)[NT]) __attribute__((always_inline)) {
 #pragma unroll
             for (int t = 0; t < NT; ++t)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) x[t][e] = xin[(int)ko[e] + noff[t]];
         };
-        half8 x_cur[NT], x_nxt[NT];
-#pragma unroll
-        for (int t = 0; t < NT; ++t) x_cur[t] = x_nxt[t] = half8{0, 0, 0, 0, 0, 0, 0, 0};
-        gather(0, x_cur);
-        for (int s0 = 0; s0 < nsteps; s0 += CONV_PD) {
+        static_assert(CONV_PD % 2 == 0, "entries and tiles alternate between two register sets");
+        ushort8 ko[2];      // list entry of step j in ko[j & 1]
+        half8 x[2][NT];     // gathered tile of step j in x[j & 1]
+        ko[0] = read_list(0);
+        gather(ko[0], x[0]);
+        ko[1] = read_list(1);
+        const int nsteps_r = (nsteps + CONV_PD - 1) / CONV_PD * CONV_PD;
+        for (int s0 = 0; s0 < nsteps_r; s0 += CONV_PD) {
 #pragma unroll
             for (int u = 0; u < CONV_PD; ++u) {
                 const int s = s0 + u;
-                if (s < nsteps) {   // uniform
-                    if (s + 1 < nsteps) {
-                        if (((s + 1) & (CONV_BULK - 1)) == 0) {
-                            // next bulk of column indices; step s is already in registers
-                            int cols[BULK_LOADS];
-                            load_cols(s + 1, cols);
-                            SHFLBW_WAVE_LDS_SYNC();   // reads of the old list are over
-                            store_koff(cols);
-                            SHFLBW_WAVE_LDS_SYNC();
-                        }
-                        gather(s + 1, x_nxt);   // in flight while step s is multiplied
+                if ((u + 2) % CONV_PD == 0) {
+                    // the entry read below may open the next bulk of column indices; every entry
+                    // of the old bulk is in registers by now
+                    if (((s + 2) & (CONV_BULK - 1)) == 0 && s + 2 < nsteps) {   // uniform
+                        int cols[BULK_LOADS];
+                        load_cols(s + 2, cols);
+                        SHFLBW_WAVE_LDS_SYNC();   // reads of the old list are over
+                        store_koff(cols);
+                        SHFLBW_WAVE_LDS_SYNC();
                     }
-#pragma unroll
-                    for (int t = 0; t < NT; ++t)
-#pragma unroll
-                        for (int rb = 0; rb < RB; ++rb)
-                            acc[rb][t] = mma32<BF>(x_cur[t], w[u][rb], acc[rb][t]);
-                    const int sn = s + CONV_PD < nsteps ? s + CONV_PD : last;
-#pragma unroll
-                    for (int rb = 0; rb < RB; ++rb) w[u][rb] = valp[((long)sn * RB + rb) * 64];
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) x_cur[t] = x_nxt[t];
                 }
+                gather(ko[(u + 1) & 1], x[(u + 1) & 1]);   // step s + 1, in flight while step s is multiplied
+                ko[u & 1] = read_list(s + 2);
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+                        acc[rb][t] = mma32<BF>(x[u & 1][t], w[u][rb], acc[rb][t]);
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) w[u][rb] = load_w(s + CONV_PD, rb);
             }
         }
     }

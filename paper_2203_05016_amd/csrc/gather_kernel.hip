@@ -35,6 +35,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "shflbw_internal.h"
 
@@ -165,12 +166,14 @@ struct GeomLinearBuf {
         ln2 = n < N ? (unsigned)n * 2u : PAST_END;
     }
 
-    __device__ __forceinline__ half8 load8(int col, long) const
+    // zero (the same for the whole wavefront): read zeros whatever the column, at the price of
+    // scalar instructions only
+    __device__ __forceinline__ half8 load8(int col, long, bool zero = false) const
     {
         typedef unsigned uint4v __attribute__((ext_vector_type(4)));
         // a lane beyond N keeps its offset past the end whatever the column
         unsigned off = __umul24((unsigned)col, ldx2) + ln2;
-        off = (col < 0 || ln2 == PAST_END) ? PAST_END : off;
+        off = (col < 0 || ln2 == PAST_END || zero) ? PAST_END : off;
         return __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(xd, (int)off, 0, 0));
     }
 
@@ -369,9 +372,13 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
                 c[i] = (int)__builtin_amdgcn_raw_buffer_load_b32(col_rsrc, (lrow + i) * 4, step * TK * 4, 0);
         }
     };
-    auto load_x = [&](const int (&c)[NLD], half8 (&x)[NLD]) {
+    // in_range false: the step lies beyond the wavefront's range and gets zeros, like a padded slot
+    auto load_x = [&](const int (&c)[NLD], half8 (&x)[NLD], bool in_range) {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) x[i] = geom.load8(c[i], ln);
+        for (int i = 0; i < NLD; ++i) {
+            if constexpr (std::is_same<Geom, GeomLinearBuf>::value) x[i] = geom.load8(c[i], ln, !in_range);
+            else x[i] = geom.load8(in_range ? c[i] : -1, ln);
+        }
     };
     auto load_w = [&](int step, half8 (&w)[RB]) {
 #pragma unroll
@@ -380,15 +387,20 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
                                                                                     (step * RB + rb) * 1024, 0));
     };
 
+    // The loop below is straight-line code over whole batches of PD steps, so that the
+    // register sets stay static and the compiler's wait counts exact (a conditional refill
+    // turns into a copy behind a full wait).  A step beyond the wavefront's range multiplies
+    // zero weights (the descriptor's range) with gathered zeros.
+    const int nsteps_r = (nsteps + PD - 1) / PD * PD;
 #pragma unroll
     for (int u = 0; u < PD; ++u) {
-        if (u < nsteps) {
-            int c0[NLD];
-            load_cols(u, c0);
-            load_x(c0, xr[u]);
-            load_w(u, wr[u]);
-        }
-        if (u + PD < nsteps) load_cols(u + PD, cols[u]);
+        int c0[NLD];
+        load_cols(u, c0);
+        load_x(c0, xr[u], u < nsteps);
+        load_cols(u + PD, cols[u]);
+        load_w(u, wr[u]);
+        // sets in the order the loop issues them: its wait counts assume set 0 is the oldest
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     // transposed-read addresses (in binary16 units inside a staged tile)
@@ -399,25 +411,22 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
     const int tr_col = S::SMALL ? (4 * (il & 3)) : (16 * (bl & 1) + 4 * (il & 3));
     const int tr_off = tr_row * PITCH + tr_col;
 
-    for (int s0 = 0; s0 < nsteps; s0 += PD) {
+    // One batch.  NEXT: the batch after this one exists, its X rows and weights are
+    // requested; AFTER: so does the one after that, whose column indices are requested.
+    // The last two batches therefore issue no loads that nobody waits for.
+    auto batch = [&](int s0, auto next_tag, auto after_tag) __attribute__((always_inline)) {
+        constexpr bool NEXT = decltype(next_tag)::value, AFTER = decltype(after_tag)::value;
 #pragma unroll
         for (int u = 0; u < PD; ++u) {
             const int s = s0 + u;
-            if (s >= nsteps) break;
             _Float16* buf = my + (s & 1) * S::STAGE;
 #pragma unroll
             for (int i = 0; i < NLD; ++i)
                 *reinterpret_cast<half8*>(buf + (lrow + i) * PITCH + lcol) = xr[u][i];
-            half8 wcur[RB];
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) wcur[rb] = wr[u][rb];
             SHFLBW_WAVE_LDS_SYNC();
 
-            if (s + PD < nsteps) {
-                load_x(cols[u], xr[u]);
-                load_w(s + PD, wr[u]);
-            }
-            if (s + 2 * PD < nsteps) load_cols(s + 2 * PD, cols[u]);
+            if (NEXT) load_x(cols[u], xr[u], AFTER || s + PD < nsteps);
+            if (AFTER) load_cols(s + 2 * PD, cols[u]);
 
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
@@ -427,17 +436,29 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
                 half4 l4 = __builtin_bit_cast(half4, lo), h4 = __builtin_bit_cast(half4, hi);
                 half8 a = {l4[0], l4[1], l4[2], l4[3], h4[0], h4[1], h4[2], h4[3]};
                 if (S::SMALL) {
-                    acc16[t] = mma16<BF>(a, wcur[0], acc16[t]);
+                    acc16[t] = mma16<BF>(a, wr[u][0], acc16[t]);
                 } else {
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb)
-                        acc32[rb][t] = mma32<BF>(a, wcur[rb], acc32[rb][t]);
+                        acc32[rb][t] = mma32<BF>(a, wr[u][rb], acc32[rb][t]);
                 }
             }
+            // refilled after its last use, so the load lands in the set's own registers
+            if (NEXT) load_w(s + PD, wr[u]);
+            // steps stay in program order: hoisting the next step's LDS writes above this
+            // step's products would make them wait for the loads issued just above
+            __builtin_amdgcn_sched_barrier(0);
             // no second sync: the next step writes the other buffer, and its own
             // sync separates these reads from the writes of the step after it
         }
+    };
+    int s0 = 0;
+    for (; s0 + 2 * PD < nsteps_r; s0 += PD) batch(s0, std::true_type{}, std::true_type{});
+    if (s0 + PD < nsteps_r) {
+        batch(s0, std::true_type{}, std::false_type{});
+        s0 += PD;
     }
+    if (s0 < nsteps_r) batch(s0, std::false_type{}, std::false_type{});
     SHFLBW_WAVE_LDS_SYNC();
 
     if (SPLIT) {
