@@ -69,7 +69,7 @@ __device__ __forceinline__ uint16_t ln_narrow(float f)
     else return __builtin_bit_cast(uint16_t, (_Float16)f);
 }
 
-template <bool BF>
+template <bool BF, bool NORM>
 __global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_kernel(LnArgs a)
 {
     __shared__ float stat_mean[LN_TOK], stat_rstd[LN_TOK];
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_kernel(LnAr
     for (int u = 0; u < LN_AHEAD; ++u) load_block(bbeg + u, ring[u]);
 
     // ---------------------------------------------------------------- phase A
-    if (a.normalize) {
+    if (NORM) {
         constexpr int TPW = LN_TOK / LN_WAVES;   // tokens per wavefront
         float s1[TPW], s2[TPW], pivot[TPW];
 #pragma unroll
@@ -173,27 +173,29 @@ __global__ __launch_bounds__(64 * LN_WAVES) void layernorm_transpose_kernel(LnAr
             const int b = b0 + u;
             if (b < bend) {   // uniform
                 const int k = b * LN_FB + lchunk * 8;
-                float g[8], bt[8];
+                if (NORM) {
+                    float g[8], bt[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) { g[e] = 1.f; bt[e] = 0.f; }
-                if (a.normalize && k < K) {
-                    if (a.gamma) {
-                        const ln_ushort8 gv = *reinterpret_cast<const ln_ushort8*>(a.gamma + k);
+                    for (int e = 0; e < 8; ++e) { g[e] = 1.f; bt[e] = 0.f; }
+                    if (k < K) {
+                        if (a.gamma) {
+                            const ln_ushort8 gv = *reinterpret_cast<const ln_ushort8*>(a.gamma + k);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) g[e] = ln_widen<BF>(gv[e]);
+                            for (int e = 0; e < 8; ++e) g[e] = ln_widen<BF>(gv[e]);
+                        }
+                        if (a.beta) {
+                            const ln_ushort8 bv = *reinterpret_cast<const ln_ushort8*>(a.beta + k);
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) bt[e] = ln_widen<BF>(bv[e]);
+                        }
                     }
-                    if (a.beta) {
-                        const ln_ushort8 bv = *reinterpret_cast<const ln_ushort8*>(a.beta + k);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) bt[e] = ln_widen<BF>(bv[e]);
-                    }
-                }
+                    for (int e = 0; e < 8; ++e)
+                        tile[(lchunk * 8 + e) * LN_PITCH + ltok] =
+                            ln_narrow<BF>((ln_widen<BF>(ring[u][e]) - mean) * rstd * g[e] + bt[e]);
+                } else {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    uint16_t o = ring[u][e];
-                    if (a.normalize)
-                        o = ln_narrow<BF>((ln_widen<BF>(o) - mean) * rstd * g[e] + bt[e]);
-                    tile[(lchunk * 8 + e) * LN_PITCH + ltok] = o;
+                    for (int e = 0; e < 8; ++e) tile[(lchunk * 8 + e) * LN_PITCH + ltok] = ring[u][e];
                 }
                 load_block(b + LN_AHEAD, ring[u]);
                 __syncthreads();
@@ -393,6 +395,166 @@ __global__ __launch_bounds__(16 * TOK) void layernorm_transpose_resident_kernel(
     }
 }
 
+// ---------------------------------------------------------------- register-resident variant
+// For feature counts whose token blocks no longer fit the LDS (up to 4096 features): a
+// workgroup of sixteen wavefronts reads its 32 tokens once and keeps them in registers
+// (two tokens per wavefront, 64 registers per lane), takes the statistics from there, and
+// passes them through the LDS in slices of 1024 features, double-buffered so that one
+// barrier per slice suffices; the transposed store of a slice is the LDS-resident
+// kernel's.  Every activation is read from HBM once, where the streaming kernel reads a
+// row once per workgroup that shares its tokens.
+template <bool BF, bool NORM>
+__global__ __launch_bounds__(1024) void layernorm_transpose_register_kernel(LnArgs a)
+{
+    constexpr int TOK = 32, WAVES = 16, TPW = 2, KMAX = 4096, SL = 1024, NSL = KMAX / SL;
+    constexpr int P = SL + 4, Q = P / 2;   // Q = 2 (mod 8): see the LDS-resident kernel
+    constexpr int CH = TOK / 8, FP = 64 / CH;
+    extern __shared__ __attribute__((aligned(16))) char ln_smem[];
+    uint16_t* xs = reinterpret_cast<uint16_t*>(ln_smem);                          // [2][TOK][P]
+    float* st_mean = reinterpret_cast<float*>(ln_smem + (size_t)2 * TOK * P * 2);  // [TOK]
+    float* st_rstd = st_mean + TOK;                                                // [TOK]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const long n0 = (long)blockIdx.x * TOK;
+    const int K = a.K;
+
+    // chunk j of a token: features j*512 + lane*8 .. +7
+    ln_ushort8 v[TPW][2 * NSL];
+    float s1[TPW], s2[TPW], pivot[TPW];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) { s1[t] = 0.f; s2[t] = 0.f; pivot[t] = 0.f; }
+    auto fetch = [&](auto full_tag) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full_tag)::value;
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            const long n = n0 + wave * TPW + t;
+#pragma unroll
+            for (int j = 0; j < 2 * NSL; ++j) {
+                const int kc = j * 512 + lane * 8;
+                if (FULL) {
+                    v[t][j] = *reinterpret_cast<const ln_ushort8*>(a.x + n * a.ldx + kc);
+                } else {
+                    v[t][j] = ln_ushort8{0, 0, 0, 0, 0, 0, 0, 0};
+                    if (n < a.N && kc < K) v[t][j] = *reinterpret_cast<const ln_ushort8*>(a.x + n * a.ldx + kc);
+                }
+            }
+        }
+        if (NORM) {
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+                pivot[t] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
+                    __builtin_bit_cast(int, ln_widen<BF>(v[t][0][0]))));
+#pragma unroll
+                for (int j = 0; j < 2 * NSL; ++j) {
+                    if (FULL || j * 512 + lane * 8 < K) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const unsigned w = (unsigned)v[t][j][2 * e] | ((unsigned)v[t][j][2 * e + 1] << 16);
+                            float d0, d1;
+                            ln_add_pair<BF>(w, -pivot[t], d0, d1);
+                            s1[t] += d0;
+                            s2[t] += d0 * d0;
+                            s1[t] += d1;
+                            s2[t] += d1 * d1;
+                        }
+                    }
+                }
+            }
+        }
+    };
+    if (n0 + TOK <= a.N && K == KMAX) fetch(std::true_type{});
+    else fetch(std::false_type{});
+    if (NORM) {
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                s1[t] += __shfl_xor(s1[t], off, 64);
+                s2[t] += __shfl_xor(s2[t], off, 64);
+            }
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+                const float m = s1[t] / (float)K;
+                float var = s2[t] / (float)K - m * m;
+                var = var > 0.f ? var : 0.f;
+                st_mean[wave * TPW + t] = pivot[t] + m;
+                st_rstd[wave * TPW + t] = 1.0f / __builtin_sqrtf(var + a.eps);
+            }
+        }
+    }
+    // slice sl of this wavefront's tokens into LDS buffer sl % 2
+    auto stage = [&](int sl) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const ln_ushort8& c = v[t][2 * sl + h];
+                uint2* dst = reinterpret_cast<uint2*>(xs + ((sl & 1) * TOK + wave * TPW + t) * P + h * 512 + lane * 8);
+                dst[0] = uint2{(unsigned)c[0] | ((unsigned)c[1] << 16), (unsigned)c[2] | ((unsigned)c[3] << 16)};
+                dst[1] = uint2{(unsigned)c[4] | ((unsigned)c[5] << 16), (unsigned)c[6] | ((unsigned)c[7] << 16)};
+            }
+        }
+    };
+    stage(0);
+    __syncthreads();
+
+    const int kk2 = lane / CH, tchunk = lane % CH;
+    float mean[8], rstd[8];
+    if (NORM) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { mean[e] = st_mean[tchunk * 8 + e]; rstd[e] = st_rstd[tchunk * 8 + e]; }
+    }
+    const long n = n0 + tchunk * 8;
+    // 1.0 twice / 0.0 twice in the 16-bit format, for absent gamma / beta
+    const unsigned one2 = BF ? 0x3f803f80u : 0x3c003c00u;
+#pragma unroll
+    for (int sl = 0; sl < NSL; ++sl) {
+        if (sl * SL < K) {   // uniform
+            // the other buffer's last readers passed the barrier that closed slice sl - 1
+            if (sl + 1 < NSL && (sl + 1) * SL < K) stage(sl + 1);
+            const unsigned* xw = reinterpret_cast<const unsigned*>(xs + (sl & 1) * TOK * P) + tchunk * 8 * Q;
+#pragma unroll
+            for (int pass = 0; pass < SL / (WAVES * 2 * FP); ++pass) {
+                const int kl = (pass * WAVES + wave) * 2 * FP + 2 * kk2;   // feature inside the slice
+                const int k = sl * SL + kl;
+                if (k < K && n < a.N) {
+                    unsigned w[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) w[e] = xw[e * Q + (kl >> 1)];
+                    ln_ushort8 o0, o1;
+                    if (NORM) {
+                        const unsigned gw = a.gamma ? *reinterpret_cast<const unsigned*>(a.gamma + k) : one2;
+                        const unsigned bw = a.beta ? *reinterpret_cast<const unsigned*>(a.beta + k) : 0u;
+                        float g0, g1, b0, b1;
+                        ln_add_pair<BF>(gw, 0.f, g0, g1);
+                        ln_add_pair<BF>(bw, 0.f, b0, b1);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            float lo, hi;
+                            ln_add_pair<BF>(w[e], -mean[e], lo, hi);
+                            o0[e] = ln_narrow<BF>(lo * rstd[e] * g0 + b0);
+                            o1[e] = ln_narrow<BF>(hi * rstd[e] * g1 + b1);
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            o0[e] = (uint16_t)(w[e] & 0xffffu);
+                            o1[e] = (uint16_t)(w[e] >> 16);
+                        }
+                    }
+                    uint16_t* dst = a.out + (long)k * a.ldo + n;
+                    __builtin_nontemporal_store(o0, reinterpret_cast<ln_ushort8*>(dst));
+                    __builtin_nontemporal_store(o1, reinterpret_cast<ln_ushort8*>(dst + a.ldo));
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
 }  // namespace
 }  // namespace shflbw
 
@@ -469,16 +631,45 @@ extern "C" int shflbw_layernorm_transpose(const void* x, int64_t ldx, const void
         if (el != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(el));
         return SHFLBW_OK;
     }
+    if (K <= 4096) {
+        // too wide for the LDS, narrow enough for the registers of sixteen wavefronts
+        typedef void (*register_fn)(LnArgs);
+        static const register_fn rtable[4] = {
+            &layernorm_transpose_register_kernel<false, false>, &layernorm_transpose_register_kernel<false, true>,
+            &layernorm_transpose_register_kernel<true, false>,  &layernorm_transpose_register_kernel<true, true>};
+        const int which = (dtype == SHFLBW_BF16 ? 2 : 0) + (a.normalize ? 1 : 0);
+        const register_fn fn = rtable[which];
+        const size_t bytes = (size_t)2 * 32 * (1024 + 4) * 2 + 2 * 32 * 4;
+        const int64_t rwgs = (N + 31) / 32;
+        if (rwgs > 0x7fffffffLL) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
+        static thread_local int raised_reg[4] = {-1, -1, -1, -1};
+        int dev = 0;
+        hipError_t ea = hipGetDevice(&dev);
+        if (ea != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(ea));
+        if (raised_reg[which] != dev) {
+            ea = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (ea != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(ea));
+            raised_reg[which] = dev;
+        }
+        hipLaunchKernelGGL(fn, dim3((unsigned)rwgs), dim3(1024), bytes, st, a);
+        hipError_t el = hipGetLastError();
+        if (el != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(el));
+        return SHFLBW_OK;
+    }
     // split the features over grid.y until there are about two workgroups per CU
     const int nblocks = (K + LN_FB - 1) / LN_FB;
     int split = 1;
     while (wgs * split < 512 && split * 2 <= nblocks && split < 16) split *= 2;
     a.blocks_per_wg = (nblocks + split - 1) / split;
     const unsigned gy = (unsigned)((nblocks + a.blocks_per_wg - 1) / a.blocks_per_wg);
-    if (dtype == SHFLBW_BF16)
-        hipLaunchKernelGGL(layernorm_transpose_kernel<true>, dim3((unsigned)wgs, gy), dim3(64 * LN_WAVES), 0, st, a);
-    else
-        hipLaunchKernelGGL(layernorm_transpose_kernel<false>, dim3((unsigned)wgs, gy), dim3(64 * LN_WAVES), 0, st, a);
+    const dim3 sgrid((unsigned)wgs, gy), sblock(64 * LN_WAVES);
+    if (dtype == SHFLBW_BF16) {
+        if (a.normalize) hipLaunchKernelGGL((layernorm_transpose_kernel<true, true>), sgrid, sblock, 0, st, a);
+        else hipLaunchKernelGGL((layernorm_transpose_kernel<true, false>), sgrid, sblock, 0, st, a);
+    } else {
+        if (a.normalize) hipLaunchKernelGGL((layernorm_transpose_kernel<false, true>), sgrid, sblock, 0, st, a);
+        else hipLaunchKernelGGL((layernorm_transpose_kernel<false, false>), sgrid, sblock, 0, st, a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
     return SHFLBW_OK;
