@@ -124,13 +124,14 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     };
     int cols0[BULK_LOADS];
     load_cols(0, cols0);   // in flight while the input box is staged
-    // so are the weight operands of the first CONV_PD steps.  Buffer loads: the descriptor
-    // covers this group's steps, a step beyond them reads as zero, so no load is conditional
+    // so are the weight operands of the first CONV_PD steps.  Buffer loads with the step in
+    // the lane offset, which the hardware checks against the descriptor's size (the scalar
+    // offset is not checked): a step beyond the group's reads as zero, so no load is conditional
     const __amdgpu_buffer_rsrc_t val_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<half8*>(a.A.values + (long)sbeg * RB * 64), 0, nsteps * RB * 1024, GATHER_BUFFER_FLAGS);
     auto load_w = [&](int s, int rb) __attribute__((always_inline)) {
-        return __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, lane * 16,
-                                                                                (s * RB + rb) * 1024, 0));
+        return __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(
+            val_rsrc, lane * 16 + (s * RB + rb) * 1024, 0, 0));
     };
     half8 w[CONV_PD][RB];
 #pragma unroll

@@ -359,17 +359,24 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
         const_cast<int32_t*>(A.col_idx + (long)sbeg * TK), 0, nsteps * TK * 4, GATHER_BUFFER_FLAGS);
     const __amdgpu_buffer_rsrc_t val_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<half8*>(A.values + (long)sbeg * RB * 64), 0, nsteps * RB * 1024, GATHER_BUFFER_FLAGS);
-    auto load_cols = [&](int step, int (&c)[NLD]) {
+    // A buffer load checks lane offset + immediate against the descriptor's size, NOT the
+    // scalar offset.  CHECKED puts the step into the lane offset, so that a step beyond the
+    // wavefront's range reads zeros instead of memory past it; the steady-state batches,
+    // whose steps all exist, keep the step in the scalar offset (no vector arithmetic).
+    auto load_cols = [&](int step, int (&c)[NLD], auto checked_tag) {
+        constexpr bool CHECKED = decltype(checked_tag)::value;
+        const int vo = CHECKED ? lrow * 4 + step * TK * 4 : lrow * 4;
+        const int so = CHECKED ? 0 : step * TK * 4;
         if (NLD == 4) {
-            uint4v v = __builtin_amdgcn_raw_buffer_load_b128(col_rsrc, lrow * 4, step * TK * 4, 0);
+            uint4v v = __builtin_amdgcn_raw_buffer_load_b128(col_rsrc, vo, so, 0);
             c[0] = (int)v[0]; c[1] = (int)v[1]; c[2] = (int)v[2]; c[3] = (int)v[3];
         } else if (NLD == 2) {
-            uint2v v = __builtin_amdgcn_raw_buffer_load_b64(col_rsrc, lrow * 4, step * TK * 4, 0);
+            uint2v v = __builtin_amdgcn_raw_buffer_load_b64(col_rsrc, vo, so, 0);
             c[0] = (int)v[0]; c[1] = (int)v[1];
         } else {
 #pragma unroll
             for (int i = 0; i < NLD; ++i)
-                c[i] = (int)__builtin_amdgcn_raw_buffer_load_b32(col_rsrc, (lrow + i) * 4, step * TK * 4, 0);
+                c[i] = (int)__builtin_amdgcn_raw_buffer_load_b32(col_rsrc, vo + i * 4, so, 0);
         }
     };
     // in_range false: the step lies beyond the wavefront's range and gets zeros, like a padded slot
@@ -380,25 +387,28 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
             else x[i] = geom.load8(in_range ? c[i] : -1, ln);
         }
     };
-    auto load_w = [&](int step, half8 (&w)[RB]) {
+    auto load_w = [&](int step, half8 (&w)[RB], auto checked_tag) {
+        constexpr bool CHECKED = decltype(checked_tag)::value;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-            w[rb] = __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, lane * 16,
-                                                                                    (step * RB + rb) * 1024, 0));
+        for (int rb = 0; rb < RB; ++rb) {
+            const int off = (step * RB + rb) * 1024;
+            w[rb] = __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(
+                val_rsrc, CHECKED ? lane * 16 + off : lane * 16, CHECKED ? 0 : off, 0));
+        }
     };
 
     // The loop below is straight-line code over whole batches of PD steps, so that the
     // register sets stay static and the compiler's wait counts exact (a conditional refill
     // turns into a copy behind a full wait).  A step beyond the wavefront's range multiplies
-    // zero weights (the descriptor's range) with gathered zeros.
+    // zero weights (range-checked loads) with gathered zeros.
     const int nsteps_r = (nsteps + PD - 1) / PD * PD;
 #pragma unroll
     for (int u = 0; u < PD; ++u) {
         int c0[NLD];
-        load_cols(u, c0);
+        load_cols(u, c0, std::true_type{});
         load_x(c0, xr[u], u < nsteps);
-        load_cols(u + PD, cols[u]);
-        load_w(u, wr[u]);
+        load_cols(u + PD, cols[u], std::true_type{});
+        load_w(u, wr[u], std::true_type{});
         // sets in the order the loop issues them: its wait counts assume set 0 is the oldest
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -426,7 +436,9 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
             SHFLBW_WAVE_LDS_SYNC();
 
             if (NEXT) load_x(cols[u], xr[u], AFTER || s + PD < nsteps);
-            if (AFTER) load_cols(s + 2 * PD, cols[u]);
+            // may name up to PD - 1 steps past the range: those indices (whatever follows in the
+            // packed matrix) are never turned into addresses
+            if (AFTER) load_cols(s + 2 * PD, cols[u], std::false_type{});
 
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
@@ -444,7 +456,8 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
                 }
             }
             // refilled after its last use, so the load lands in the set's own registers
-            if (NEXT) load_w(s + PD, wr[u]);
+            // the last loading batch may reach past the range: checked there
+            if (NEXT) load_w(s + PD, wr[u], std::integral_constant<bool, !AFTER>{});
             // steps stay in program order: hoisting the next step's LDS writes above this
             // step's products would make them wait for the loads issued just above
             __builtin_amdgcn_sched_barrier(0);

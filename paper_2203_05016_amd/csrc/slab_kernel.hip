@@ -250,7 +250,8 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     const int last = nsteps - 1;
     // Buffer loads: the descriptor holds the group's base address, the step's offset goes in a
     // scalar register and the lane's in one vector register, so a load costs no vector
-    // arithmetic.  Offsets beyond the group's steps would read as zero.
+    // arithmetic.  The hardware checks only the lane offset against the descriptor's size, so
+    // the step index is kept in range by the code (the refills clamp it to the last step).
     typedef unsigned uint4v __attribute__((ext_vector_type(4)));
     constexpr int WPS = TK / 2;                       // table words per step
     const __amdgpu_buffer_rsrc_t tab_rsrc = __builtin_amdgcn_make_buffer_rsrc(

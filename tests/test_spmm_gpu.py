@@ -165,6 +165,26 @@ def test_large_magnitudes_and_signed_zero():
     assert_within_scaled_tolerance(Y, Yr, S, what="magnitudes")
 
 
+@pytest.mark.parametrize("kernel", [0, 1, 2])
+def test_infinite_weights_stay_in_their_group(kernel):
+    """Three k-steps per group (an odd count: the kernels' batches of steps
+    run past the group's end) and a middle group whose weights are all
+    infinite: the steps past the end must multiply zeros, not the
+    neighbour's weights, so the other groups' rows stay finite and right."""
+    announce("infinite neighbour", kernel)
+    V = 32
+    p = synth.make_spmm(3 * V, 96, 72, V, 0.5, seed=87)
+    rows_mid = p.perm[V:2 * V]
+    others = np.concatenate([p.perm[:V], p.perm[2 * V:]])
+    p.W[rows_mid, :] = np.float16(np.inf)
+    Y = run_spmm(p, out_dtype="float32", kernel=kernel)
+    assert not np.isfinite(Y[rows_mid]).any()
+    Wf = p.W.copy()
+    Wf[rows_mid, :] = 0
+    Yr, S = c_oracle.spmm(Wf, p.mask, p.X)
+    assert_within_scaled_tolerance(Y[others], Yr[others], S[others], what="rows beside an infinite group")
+
+
 def test_config3_attention_projection_sampled():
     """Config 3 at V=32, 75 %: full launch on the GPU, oracle on a column
     sample (every row, 96 sampled columns incl. both ends)."""
