@@ -94,12 +94,38 @@ def time_steps(fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
+def time_graph(fn, per_graph, replays):
+    """Average milliseconds per call of fn when `per_graph` calls are captured into one HIP
+    graph and the graph is replayed: what a launch costs once the host's issue rate is out
+    of the way (a product of a few microseconds is otherwise bound by it)."""
+    import torch
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for _ in range(per_graph):
+            fn()
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(per_graph):
+            fn()
+    graph.replay()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (replays * per_graph)
+
+
 def rotation_for(p, out_bytes=2, cache=256 << 20):
     per = 2 * p.K * p.N + out_bytes * p.M * p.N
     return max(2, min(8, -(-2 * cache // per)))
 
 
-def measure_spmm(p, steps, warmup, cold=True, **kw):
+def measure_spmm(p, steps, warmup, cold=True, graph=False, **kw):
     import torch
     rot = rotation_for(p) if cold else 1
     c = Case(p, rot, **kw)
@@ -108,6 +134,10 @@ def measure_spmm(p, steps, warmup, cold=True, **kw):
     r = dict(ms=ms, tflops=c.flop() / (ms * 1e-3) / 1e12, gbps=c.bytes() / (ms * 1e-3) / 1e9,
              nnz=c.info["nnz"], sparsity=c.info["sparsity"], bytes=c.bytes(), flop=c.flop(),
              rotate=rot)
+    if graph:
+        # the same launches, rotating operands included, replayed from a HIP graph
+        r["graph_ms"] = time_graph(c.step, 4 * rot, max(1, steps // (4 * rot)))
+        c.A.device_status()
     del c
     torch.cuda.empty_cache()
     return r
@@ -339,7 +369,7 @@ def main():
         extra = {}
         for variant in range(9):
             q = synth.config(2, variant=variant)
-            r = measure_spmm(q, args.steps, args.warmup, cold=True)
+            r = measure_spmm(q, args.steps, args.warmup, cold=True, graph=True)
             d = measure_spmm(synth.config(2, variant=variant, sparsity=0.0), args.steps // 2 or 1,
                              args.warmup, cold=True)
             extra["config3_V%d_s%.2f" % (q.V, r["sparsity"])] = dict(r, dense_ms=d["ms"],
@@ -352,7 +382,7 @@ def main():
         # matrix-vector-like regime (recurrent layers): few output columns
         for (M, K, N, V, sp) in ((4096, 4096, 64, 32, 0.75), (4096, 1024, 128, 32, 0.75)):
             q = synth.make_spmm(M, K, N, V, sp, seed=synth.BASE_SEED + 7000 + N)
-            r = measure_spmm(q, args.steps, args.warmup, cold=True)
+            r = measure_spmm(q, args.steps, args.warmup, cold=True, graph=True)
             r1 = measure_spmm(q, args.steps, args.warmup, cold=True, kernel=1)
             extra["skinny_%dx%dx%d_s%.2f" % (M, K, N, sp)] = dict(r, whole_tile_gather_ms=r1["ms"])
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)

@@ -185,6 +185,47 @@ def test_infinite_weights_stay_in_their_group(kernel):
     assert_within_scaled_tolerance(Y[others], Yr[others], S[others], what="rows beside an infinite group")
 
 
+@pytest.mark.parametrize("kernel", [1, 2])
+def test_launches_replayed_from_a_graph_match_eager(kernel):
+    """shflbw_spmm only enqueues a kernel on the caller's stream (no
+    allocation, no synchronisation, no memset), so its launches can be captured
+    into a HIP graph; every replay, with eager launches and synchronisations
+    in between, must reproduce the eager result bit for bit."""
+    import torch
+    from paper_2203_05016_amd import binding
+    from gpu_util import to_device, to_host
+    announce("graph replay", kernel)
+    p = synth.make_spmm(256, 512, 384, 32, 0.75, seed=91)
+    A = binding.compress(p.W, p.mask, p.perm, p.V)
+    A.set_tuning(kernel, 0)
+    A.bind_device("cuda:0")
+    X = to_device(p.X)
+    X2 = to_device(synth.make_spmm(256, 512, 384, 32, 0.75, seed=92).X)
+    eager = torch.empty((p.M, p.N), dtype=torch.float16, device="cuda:0")
+    A.spmm(X, eager)
+    torch.cuda.synchronize()
+    want = to_host(eager).view(np.uint16)
+    Yg = torch.zeros((p.M, p.N), dtype=torch.float16, device="cuda:0")
+    Xg = X.clone()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        A.spmm(Xg, Yg)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        A.spmm(Xg, Yg)
+        A.spmm(Xg, Yg)
+    for replay in range(4):
+        Yg.fill_(float("nan"))
+        other = torch.empty_like(eager)
+        A.spmm(X2, other)               # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(Yg).view(np.uint16), want), "replay %d" % replay
+    A.device_status()
+
+
 def test_config3_attention_projection_sampled():
     """Config 3 at V=32, 75 %: full launch on the GPU, oracle on a column
     sample (every row, 96 sampled columns incl. both ends)."""
