@@ -321,7 +321,7 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
         const double density = (double)A->nnz / ((double)A->M * A->K);
         // (crossovers measured at 85 % sparsity for V = 16 and 32, 78-80 % for V = 64, whose
         // gathered bytes serve twice the rows)
-        const double need = tiles >= 128 ? (A->V == 64 ? 0.22 : 0.15) : 0.6;
+        const double need = tiles >= 128 ? (A->V == 64 ? 0.22 : 0.17) : 0.6;
         // very few column tiles: the gather kernel with split k-steps fills the chip better
         const bool skinny = ((N + 63) / 64) * A->G <= 512;
         use_slab = A->G >= gw && density >= need && !skinny;
