@@ -401,12 +401,13 @@ __global__ __launch_bounds__(16 * TOK) void layernorm_transpose_resident_kernel(
 // 64 registers per lane), takes the statistics from there, and passes them through the
 // LDS in slices of 1024 features, double-buffered so that one barrier per slice suffices;
 // the transposed store of a slice is the LDS-resident kernel's.  Up to 4096 features
-// (HALVES = 1) every activation is read from HBM once.  Up to 8192 (HALVES = 2) the
-// statistics sweep reads both halves, the second stays in registers and goes out first,
-// and the first half is read again (1.5 reads per activation; the streaming kernel reads
-// a row once per workgroup that shares its tokens, and 16-token blocks, whose 32-byte
-// row segments halve the write rate, measured 187 us against 112 on 8192 x 8192).
-template <bool BF, bool NORM, int HALVES>
+// (PARTS = 1) every activation is read from HBM once.  Wider rows (PARTS = 2 .. 4, up to
+// 16384 features) are swept in parts of 4096 for the statistics; the last part stays in
+// registers and goes out first, the others are read again (2 - 1/PARTS reads per
+// activation; the streaming kernel reads a row once per workgroup that shares its
+// tokens, and 16-token blocks, whose 32-byte row segments halve the write rate, measured
+// 187 us against 112 on 8192 x 8192).
+template <bool BF, bool NORM, int PARTS>
 __global__ __launch_bounds__(1024) void layernorm_transpose_register_kernel(LnArgs a)
 {
     constexpr int TOK = 32, WAVES = 16, TPW = 2, KH = 4096, SL = 1024, NSL = KH / SL;
@@ -421,16 +422,16 @@ __global__ __launch_bounds__(1024) void layernorm_transpose_register_kernel(LnAr
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const long n0 = (long)blockIdx.x * TOK;
     const int K = a.K;
-    const bool full = n0 + TOK <= a.N && K == KH * HALVES;
+    const bool full = n0 + TOK <= a.N && K == KH * PARTS;
 
-    // chunk j of a token's half: features half*4096 + j*512 + lane*8 .. +7
+    // chunk j of a token's part: features part*4096 + j*512 + lane*8 .. +7
     ln_ushort8 v[TPW][2 * NSL];
     float s1[TPW], s2[TPW], pivot[TPW];
 #pragma unroll
     for (int t = 0; t < TPW; ++t) { s1[t] = 0.f; s2[t] = 0.f; pivot[t] = 0.f; }
-    auto fetch_as = [&](int half, auto full_tag, auto stats_tag) __attribute__((always_inline)) {
+    auto fetch_as = [&](int part, auto full_tag, auto stats_tag) __attribute__((always_inline)) {
         constexpr bool FULL = decltype(full_tag)::value, STATS = decltype(stats_tag)::value;
-        const int kh = half * KH;
+        const int kh = part * KH;
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
             const long n = n0 + wave * TPW + t;
@@ -448,7 +449,7 @@ __global__ __launch_bounds__(1024) void layernorm_transpose_register_kernel(LnAr
         if (STATS) {
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
-                if (half == 0)
+                if (part == 0)
                     pivot[t] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
                         __builtin_bit_cast(int, ln_widen<BF>(v[t][0][0]))));
 #pragma unroll
@@ -469,9 +470,9 @@ __global__ __launch_bounds__(1024) void layernorm_transpose_register_kernel(LnAr
             }
         }
     };
-    auto fetch = [&](int half, auto stats_tag) __attribute__((always_inline)) {
-        if (full) fetch_as(half, std::true_type{}, stats_tag);
-        else fetch_as(half, std::false_type{}, stats_tag);
+    auto fetch = [&](int part, auto stats_tag) __attribute__((always_inline)) {
+        if (full) fetch_as(part, std::true_type{}, stats_tag);
+        else fetch_as(part, std::false_type{}, stats_tag);
     };
 
     const int kk2 = lane / CH, tchunk = lane % CH;
@@ -479,9 +480,9 @@ __global__ __launch_bounds__(1024) void layernorm_transpose_register_kernel(LnAr
     float mean[8], rstd[8];
     // 1.0 twice in the 16-bit format, for an absent gamma
     const unsigned one2 = BF ? 0x3f803f80u : 0x3c003c00u;
-    // the half held in registers, slice by slice through the LDS, out as transposed rows
-    auto emit = [&](int half) __attribute__((always_inline)) {
-        const int kh = half * KH;
+    // the part held in registers, slice by slice through the LDS, out as transposed rows
+    auto emit = [&](int part) __attribute__((always_inline)) {
+        const int kh = part * KH;
         auto stage = [&](int sl) __attribute__((always_inline)) {
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
@@ -542,16 +543,16 @@ __global__ __launch_bounds__(1024) void layernorm_transpose_register_kernel(LnAr
     };
 
     if (!NORM) {
-        // nothing to wait for: each half goes out as it comes in
+        // nothing to wait for: each part goes out as it comes in
 #pragma unroll
-        for (int half = 0; half < HALVES; ++half) {
-            fetch(half, std::false_type{});
-            emit(half);
+        for (int part = 0; part < PARTS; ++part) {
+            fetch(part, std::false_type{});
+            emit(part);
         }
         return;
     }
 #pragma unroll
-    for (int half = 0; half < HALVES; ++half) fetch(half, std::true_type{});
+    for (int part = 0; part < PARTS; ++part) fetch(part, std::true_type{});
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
 #pragma unroll
@@ -573,10 +574,11 @@ __global__ __launch_bounds__(1024) void layernorm_transpose_register_kernel(LnAr
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < 8; ++e) { mean[e] = st_mean[tchunk * 8 + e]; rstd[e] = st_rstd[tchunk * 8 + e]; }
-    emit(HALVES - 1);   // the half the sweep left in the registers
-    if (HALVES == 2) {
-        fetch(0, std::false_type{});
-        emit(0);
+    emit(PARTS - 1);   // the part the sweep left in the registers
+#pragma unroll
+    for (int part = 0; part < PARTS - 1; ++part) {
+        fetch(part, std::false_type{});
+        emit(part);
     }
 }
 
@@ -656,20 +658,22 @@ extern "C" int shflbw_layernorm_transpose(const void* x, int64_t ldx, const void
         if (el != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(el));
         return SHFLBW_OK;
     }
-    if (K <= 8192) {
-        // too wide for the LDS, narrow enough for the registers of sixteen wavefronts
+    if (K <= 16384) {
+        // too wide for the LDS, narrow enough to go through the registers of sixteen wavefronts
+        // in at most four parts
         typedef void (*register_fn)(LnArgs);
-        static const register_fn rtable[8] = {
-            &layernorm_transpose_register_kernel<false, false, 1>, &layernorm_transpose_register_kernel<false, true, 1>,
-            &layernorm_transpose_register_kernel<true, false, 1>,  &layernorm_transpose_register_kernel<true, true, 1>,
-            &layernorm_transpose_register_kernel<false, false, 2>, &layernorm_transpose_register_kernel<false, true, 2>,
-            &layernorm_transpose_register_kernel<true, false, 2>,  &layernorm_transpose_register_kernel<true, true, 2>};
-        const int which = (K > 4096 ? 4 : 0) + (dtype == SHFLBW_BF16 ? 2 : 0) + (a.normalize ? 1 : 0);
+#define SHFLBW_LN_REG(P) \
+    &layernorm_transpose_register_kernel<false, false, P>, &layernorm_transpose_register_kernel<false, true, P>, \
+    &layernorm_transpose_register_kernel<true, false, P>, &layernorm_transpose_register_kernel<true, true, P>
+        static const register_fn rtable[16] = {SHFLBW_LN_REG(1), SHFLBW_LN_REG(2), SHFLBW_LN_REG(3), SHFLBW_LN_REG(4)};
+#undef SHFLBW_LN_REG
+        const int parts = (K + 4095) / 4096;
+        const int which = (parts - 1) * 4 + (dtype == SHFLBW_BF16 ? 2 : 0) + (a.normalize ? 1 : 0);
         const register_fn fn = rtable[which];
         const size_t bytes = (size_t)2 * 32 * (1024 + 4) * 2 + 2 * 32 * 4;
         const int64_t rwgs = (N + 31) / 32;
         if (rwgs > 0x7fffffffLL) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
-        static thread_local int raised_reg[8] = {-1, -1, -1, -1, -1, -1, -1, -1};
+        static thread_local int raised_reg[16] = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1};
         int dev = 0;
         hipError_t ea = hipGetDevice(&dev);
         if (ea != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(ea));

@@ -40,13 +40,12 @@ def _check(x, gamma, beta, eps, fmt):
 
 @pytest.mark.parametrize("fmt", ["f16", "bf16"])
 @pytest.mark.parametrize("N,K", [(64, 64), (200, 1024), (1000, 328), (8, 8), (72, 4096), (16456, 72),
-                                 (96, 2264), (96, 2272), (40008, 1024), (200, 3000), (72, 4104), (40, 8192), (24, 8200)])
+                                 (96, 2264), (96, 2272), (40008, 1024), (200, 3000), (72, 4104), (40, 8192), (24, 8200), (40, 16384), (16, 16392)])
 def test_layernorm_transpose_parity(fmt, N, K):
     """Shapes for each code path: blocks of 32 tokens held in LDS, blocks of 64
     (input and output beyond 160 MB, ragged last block), the largest K that
-    still fits, the register-resident kernel beyond it (32 tokens up to 4096
-    features, 16 tokens up to 8192; full and partial slices) and the streaming
-    kernel beyond that."""
+    still fits, the register-resident kernel beyond it (one to four parts of
+    4096 features, full and partial) and the streaming kernel beyond 16384."""
     announce("layernorm", fmt, N, K)
     x, gamma, beta = _draw(N, K, fmt, seed=700 + N + K)
     _check(x, gamma, beta, 1e-5, fmt)
