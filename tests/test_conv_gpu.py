@@ -93,6 +93,27 @@ def test_conv_staged_kernel_box_shapes(layout, batch, Cin, H, Wd, Cout, V):
     _parity(p, kernel=1)
 
 
+@pytest.mark.parametrize("kernel", [1, 2])
+def test_conv_infinite_weights_stay_in_their_group(kernel):
+    """Groups of 5 k-steps (the step loops run whole batches and so reach
+    past a group's end) beside a group whose weights are all infinite: the
+    steps past the end must multiply zeros, not the neighbour's weights."""
+    announce("conv infinite neighbour", kernel)
+    V = 32
+    p = synth.make_conv(2, 16, 9, 9, 3 * V, 3, 3, V, 0.45, seed=231, pad=(1, 1))   # 79 kept columns
+    g = p.conv
+    rows_mid = p.perm[V:2 * V]
+    others = np.concatenate([p.perm[:V], p.perm[2 * V:]])
+    p.W[rows_mid, :] = np.float16(np.inf)
+    got = _run_conv(p, out_dtype="float32", kernel=kernel)
+    assert not np.isfinite(got[:, rows_mid]).any()
+    Wf = p.W.copy()
+    Wf[rows_mid, :] = 0
+    want, sc = c_oracle.conv2d(Wf, p.mask, g["input"], g["R"], g["S"], g["stride"], g["pad"], g["layout"])
+    assert_within_scaled_tolerance(got[:, others], want[:, others], sc[:, others],
+                                   what="channels beside an infinite group")
+
+
 def test_conv_staged_kernel_refuses_what_it_cannot_hold():
     """Forcing the staged kernel on V = 16 is an error, not a silent switch."""
     announce("conv staged refusal")
