@@ -184,8 +184,8 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
  *  in   device, the matrix's wdtype: [batch][C_in][H][W] (NCHW) or [C_in][H][W][batch] (CHWN).
  *  out  device, ydtype (the matrix's wdtype, or SHFLBW_F32): [batch][C_out][H_out][W_out] or [C_out][H_out][W_out][batch],
  *       H_out = (H + 2*pad_h - R)/stride_h + 1, W_out likewise.
- * For V = 32 and 64 a workgroup copies the part of the input its output
- * positions can touch into LDS once and gathers from there; other V, and
+ * For V = 32, 64 and 128 a workgroup copies the part of the input its output
+ * positions can touch into LDS once and gathers from there; V = 16, and
  * inputs with too many channels for that, take the per-wave gather kernel.
  */
 int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out,

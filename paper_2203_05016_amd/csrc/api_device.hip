@@ -96,7 +96,7 @@ int check_ydtype(const shflbw_matrix* A, shflbw_dtype ydtype)
 bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S, int sh, int sw,
                int ph, int pw, int Ho, int Wo, bool chwn, ConvArgs& a, size_t& lds_bytes)
 {
-    if (A->V != 32 && A->V != 64) return false;
+    if (A->V != 32 && A->V != 64 && A->V != 128) return false;
     if (A->K >= (1 << 20) || (long)R * S >= (1 << 20)) return false;   // exact division by multiplication
     const int gblocks = (A->G + CONV_GW - 1) / CONV_GW;
     const size_t list_bytes = CONV_LIST_BYTES;   // per-wavefront lists of LDS offsets
@@ -121,6 +121,7 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     bool found = false;
     const int targets[3] = {CONV_TN, 64, 32};
     for (int target : targets) {
+        if (A->V == 128 && target > 64) continue;   // four row blocks: accumulators for two instruction tiles at most
         double best_cost = 0;
         int bh = 0, bw = 0, bb = 0;
         for (int b = 1; b <= B && b <= target; b = (b < B && 2 * b > B) ? B : 2 * b) {
@@ -203,7 +204,8 @@ int launch_conv(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStream
     const int npos = a.tb * a.th * a.tw;
     if (npos <= 32) return launch_conv_nt<V, 1, OutT, BF>(A, a, lds_bytes, stream);
     if (npos <= 64) return launch_conv_nt<V, 2, OutT, BF>(A, a, lds_bytes, stream);
-    return launch_conv_nt<V, 4, OutT, BF>(A, a, lds_bytes, stream);
+    if constexpr (V <= 64) return launch_conv_nt<V, 4, OutT, BF>(A, a, lds_bytes, stream);
+    else return fail(SHFLBW_ERR_BAD_SHAPE, "box too large for V = 128");   // plan_conv never asks for it
 }
 
 template <int V>
@@ -222,7 +224,8 @@ int dispatch_conv(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, shflbw_
                   hipStream_t stream)
 {
     if (A->V == 32) return dispatch_conv_v<32>(A, a, lds_bytes, ydtype, stream);
-    return dispatch_conv_v<64>(A, a, lds_bytes, ydtype, stream);
+    if (A->V == 64) return dispatch_conv_v<64>(A, a, lds_bytes, ydtype, stream);
+    return dispatch_conv_v<128>(A, a, lds_bytes, ydtype, stream);
 }
 
 int check_bound(const shflbw_matrix* A)
@@ -408,7 +411,7 @@ int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, 
         }
         if (A->tune_kernel == 2)
             return fail(SHFLBW_ERR_BAD_OPTION,
-                        "staged convolution kernel needs V = 32 or 64 and an input box that fits the LDS");
+                        "staged convolution kernel needs V = 32, 64 or 128 and an input box that fits the LDS");
     }
     GeomConv g;
     g.in = static_cast<const _Float16*>(in);

@@ -17,7 +17,7 @@
 // all-zero channel plane.
 //
 // Algorithm 1's parts: BulkLoadMeta = column indices in bulks of 64 k-steps,
-// the weight operand eight (V = 64: four) k-steps ahead in as many register sets;
+// the weight operand eight (V = 64: four, V = 128: two) k-steps ahead in as many register sets;
 // StitchTile = the LDS gather above (each lane reads the 8 reduction indices
 // x up to 4 positions it feeds to the matrix cores); WarpMMA =
 // v_mfma_f32_32x32x16_f16 with the activation tile as first operand;
@@ -72,7 +72,7 @@ template <int V, int NT, typename OutT, bool BF>
 __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
 {
     constexpr int RB = V / 32;
-    constexpr int CONV_PD = RB == 1 ? 8 : 4;   // k-steps the weight operand is fetched ahead
+    constexpr int CONV_PD = RB == 1 ? 8 : RB == 2 ? 4 : 2;   // k-steps the weight operand is fetched ahead
     static_assert(CONV_BULK % CONV_PD == 0, "bulk boundaries fall on batch boundaries");
     extern __shared__ __attribute__((aligned(16))) char conv_smem[];
     _Float16* xin = reinterpret_cast<_Float16*>(conv_smem);

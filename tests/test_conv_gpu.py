@@ -49,13 +49,13 @@ def test_conv_small_shapes(layout, stride, pad, R, S):
     _parity(p, out_dtype="float32", tile_n=64, kernel=1)
 
 
-@pytest.mark.parametrize("V", [16, 64])
+@pytest.mark.parametrize("V", [16, 64, 128])
 def test_conv_other_group_sizes_integer_exact(V):
     announce("conv integer", V)
     p = synth.make_conv(2, 16, 7, 7, 2 * V, 3, 3, V, 0.75, seed=202, pad=(1, 1), integer=True)
     g = p.conv
     got = _run_conv(p, out_dtype="float32")
-    if V == 64:  # the staged kernel covers V = 32 and 64; both kernels must agree bit for bit
+    if V >= 64:  # the staged kernel covers V = 32, 64 and 128; both kernels must agree bit for bit
         assert np.array_equal(got, _run_conv(p, out_dtype="float32", kernel=1))
         assert np.array_equal(got, _run_conv(p, out_dtype="float32", kernel=2))
     want, _ = c_oracle.conv2d(p.W, p.mask, g["input"], 3, 3, (1, 1), (1, 1))
@@ -85,6 +85,8 @@ def test_conv_1x1_equals_spmm_path_bitwise():
     ("NCHW", 4, 8, 96, 96, 32, 32),     # enough positions for boxes of 128 (four instruction tiles)
     ("NCHW", 4, 8, 72, 72, 32, 32),     # boxes of 64 (two instruction tiles)
     ("CHWN", 16, 8, 48, 48, 64, 64),    # batch innermost, boxes of 128, V = 64
+    ("NCHW", 4, 8, 72, 72, 256, 128),   # V = 128: four row blocks, boxes of 64 at most
+    ("CHWN", 24, 12, 9, 9, 128, 128),   # V = 128, batch innermost, one group
 ])
 def test_conv_staged_kernel_box_shapes(layout, batch, Cin, H, Wd, Cout, V):
     announce("conv boxes", layout, batch, Cin, H, Wd, Cout, V)
