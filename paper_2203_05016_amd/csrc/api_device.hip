@@ -98,7 +98,9 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
 {
     if (A->V != 32 && A->V != 64 && A->V != 128) return false;
     if (A->K >= (1 << 20) || (long)R * S >= (1 << 20)) return false;   // exact division by multiplication
-    const int gblocks = (A->G + CONV_GW - 1) / CONV_GW;
+    // up to four groups: the wavefronts left over share a group's instruction tiles
+    const int gpb = A->G <= 4 ? (A->G > 0 ? A->G : 1) : CONV_GW;
+    const int gblocks = (A->G + gpb - 1) / gpb;
     const size_t list_bytes = CONV_LIST_BYTES;   // per-wavefront lists of LDS offsets
     const size_t lds_cap = 160 * 1024 - 512;
     const double kg_avg = A->G > 0 ? (double)A->nnz / ((double)A->V * A->G) : 0.0;
@@ -164,6 +166,13 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     a.rows_in = (th - 1) * sh + R; a.cols_in = (tw - 1) * sw + S;
     a.b_fast = chwn ? 1 : 0;
     a.gblocks = gblocks;
+    a.gpb = gpb;
+    {
+        const int tiles = (th * tw * tb + 31) / 32;
+        const int spare = CONV_GW / gpb;   // wavefronts per group
+        a.tsplit = spare < tiles ? spare : tiles;
+        if (a.tsplit == 3) a.tsplit = 2;   // tiles per wavefront come as 1, 2 or 4
+    }
     auto magic = [](int d) { return (((unsigned long long)1 << 40) + d - 1) / (unsigned long long)d; };
     a.m_RS = magic(R * S); a.m_S = magic(S); a.m_tb = magic(tb); a.m_cols_in = magic(a.cols_in);
     a.m_tw = magic(tw); a.m_th = magic(th);
@@ -201,7 +210,8 @@ int launch_conv_nt(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStr
 template <int V, typename OutT, bool BF>
 int launch_conv(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStream_t stream)
 {
-    const int npos = a.tb * a.th * a.tw;
+    const int tiles = (a.tb * a.th * a.tw + 31) / 32;
+    const int npos = (tiles + a.tsplit - 1) / a.tsplit * 32;   // positions one wavefront covers
     if (npos <= 32) return launch_conv_nt<V, 1, OutT, BF>(A, a, lds_bytes, stream);
     if (npos <= 64) return launch_conv_nt<V, 2, OutT, BF>(A, a, lds_bytes, stream);
     if constexpr (V <= 64) return launch_conv_nt<V, 4, OutT, BF>(A, a, lds_bytes, stream);

@@ -55,7 +55,8 @@ struct ConvArgs {
     int ny, nx, nb;           // boxes along y, x, batch
     int rows_in, cols_in;     // input rows / columns one box can touch
     int b_fast;               // 1: batch runs fastest in the local index (CHWN)
-    int gblocks;              // blocks of CONV_GW groups
+    int gblocks;              // blocks of gpb groups
+    int gpb, tsplit;          // groups per workgroup; wavefronts that share a group's instruction tiles
     int in_bytes;             // LDS bytes reserved for the staged input (and the scratch)
     // ceil(2^40 / d) for the divisors the kernel needs: x / d == (x * m) >> 40 for x, d < 2^20
     unsigned long long m_RS, m_S, m_tb, m_cols_in, m_tw, m_th;
@@ -67,7 +68,7 @@ __device__ __forceinline__ int conv_div(int x, unsigned long long m)
     return (int)(((unsigned long long)(unsigned)x * m) >> 40);
 }
 
-// NT: 32-position instruction tiles per box (1, 2 or 4; a box holds at most 32*NT positions).
+// NT: 32-position instruction tiles per wavefront (1, 2 or 4; a box holds at most 32*NT*tsplit positions).
 template <int V, int NT, typename OutT, bool BF>
 __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
 {
@@ -93,8 +94,11 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     const int zero_off = a.C * plane;
     const int RS = a.R * a.S;
 
-    const int g = gb * CONV_GW + wave;
-    const bool have_group = g < a.A.G;
+    // wavefront -> (group of the block, share of the box's instruction tiles): with few row
+    // groups the wavefronts left over split the positions of the box instead of idling
+    const int gi = wave % a.gpb, ts = wave / a.gpb;
+    const int g = gb * a.gpb + gi;
+    const bool have_group = g < a.A.G && ts < a.tsplit;
     const int sbeg = have_group ? a.A.step_ptr[g] : 0;
     const int nsteps = have_group ? a.A.step_ptr[g + 1] - sbeg : 0;
 
@@ -168,13 +172,13 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     store_koff(cols0);
     __syncthreads();
 
-    // ---- this lane's output positions: n' = 32*t + lane%32
+    // ---- this lane's output positions: n' = 32*(ts*NT + t) + lane%32
     const int npos = a.tb * a.th * a.tw;
     int noff[NT], ooff[NT];
     bool live[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        const int n = 32 * t + (lane & 31);
+        const int n = 32 * (ts * NT + t) + (lane & 31);
         int bb, yy, xx;
         if (a.b_fast) {
             const int q = conv_div(n, a.m_tb);
