@@ -98,6 +98,9 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
 {
     if (A->V != 32 && A->V != 64 && A->V != 128) return false;
     if (A->K >= (1 << 20) || (long)R * S >= (1 << 20)) return false;   // exact division by multiplication
+    // the kernel addresses the input through a buffer descriptor with 32-bit byte offsets
+    const unsigned long long in_total = 2ULL * (unsigned long long)B * C * H * W;
+    if (in_total >= 0xffffff00ULL) return false;
     // up to four groups: the wavefronts left over share a group's instruction tiles
     const int gpb = A->G <= 4 ? (A->G > 0 ? A->G : 1) : CONV_GW;
     const int gblocks = (A->G + gpb - 1) / gpb;
@@ -166,6 +169,7 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     a.rows_in = (th - 1) * sh + R; a.cols_in = (tw - 1) * sw + S;
     a.b_fast = chwn ? 1 : 0;
     a.gblocks = gblocks;
+    a.in_bytes_total = (unsigned)in_total;
     a.gpb = gpb;
     {
         const int tiles = (th * tw * tb + 31) / 32;

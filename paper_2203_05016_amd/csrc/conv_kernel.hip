@@ -58,6 +58,7 @@ struct ConvArgs {
     int gblocks;              // blocks of gpb groups
     int gpb, tsplit;          // groups per workgroup; wavefronts that share a group's instruction tiles
     int in_bytes;             // LDS bytes reserved for the staged input (and the scratch)
+    unsigned in_bytes_total;  // bytes of the whole input tensor (below 2^32 - 64: the host checks)
     // ceil(2^40 / d) for the divisors the kernel needs: x / d == (x * m) >> 40 for x, d < 2^20
     unsigned long long m_RS, m_S, m_tb, m_cols_in, m_tw, m_th;
 };
@@ -146,25 +147,32 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     }
 
     // ---- stage the input box: element (c, iy, ix, bb) at xin[c*plane + (iy*cols_in + ix)*tb + bb]
+    // Branch-free: the input sits behind a buffer descriptor, an element outside the image
+    // (padding, ragged boxes) or a channel beyond C gets an offset past its end and reads as
+    // zero; a channel beyond C is written onto the all-zero plane, which is channel C.
+    const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<_Float16*>(a.in), 0, (int)a.in_bytes_total, GATHER_BUFFER_FLAGS);
+    constexpr unsigned IN_PAST_END = 0xfffffff0u;
+    const unsigned isC2 = (unsigned)a.isC * 2u;
     for (int p = lane; p < plane; p += 64) {
         const int q = conv_div(p, a.m_tb), bb = p - q * a.tb;
         const int iy = conv_div(q, a.m_cols_in), ix = q - iy * a.cols_in;
         const int yy = iy0 + iy, xx = ix0 + ix, b = b0 + bb;
         const bool inside = yy >= 0 && yy < a.H && xx >= 0 && xx < a.W && b < a.B;
-        const _Float16* src = a.in + (inside ? b * a.isB + yy * a.isH + xx * a.isW : 0);
+        const unsigned base = (unsigned)(b * a.isB + yy * a.isH + xx * a.isW) * 2u;
         constexpr int MLP = 16;   // loads in flight per lane
         for (int c0 = wave; c0 < a.C; c0 += CONV_GW * MLP) {
-            _Float16 v[MLP];
+            unsigned short v[MLP];
 #pragma unroll
             for (int j = 0; j < MLP; ++j) {
                 const int c = c0 + j * CONV_GW;
-                v[j] = (_Float16)0.f;
-                if (inside && c < a.C) v[j] = src[c * a.isC];
+                const unsigned off = (inside && c < a.C) ? base + (unsigned)c * isC2 : IN_PAST_END;
+                v[j] = __builtin_amdgcn_raw_buffer_load_b16(in_rsrc, (int)off, 0, 0);
             }
 #pragma unroll
             for (int j = 0; j < MLP; ++j) {
                 const int c = c0 + j * CONV_GW;
-                if (c < a.C) xin[c * plane + p] = v[j];
+                reinterpret_cast<unsigned short*>(xin)[(c < a.C ? c : a.C) * plane + p] = v[j];
             }
         }
         if (wave == 0) xin[zero_off + p] = (_Float16)0.f;   // the all-zero plane
