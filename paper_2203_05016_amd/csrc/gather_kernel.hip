@@ -192,6 +192,40 @@ struct GeomLinearBuf {
     }
 };
 
+// 1x1 convolution with unit stride and no padding on NCHW tensors (Section 4.1's
+// implicit GEMM with R = S = 1): image b is a row-major [K][HW] matrix, so column
+// n = b*HW + hw of the product lives at X + (b*K + k)*HW + hw, and its output at
+// Y + (b*M + row)*HW + hw.  The loads are GeomLinearBuf's with a per-lane image base;
+// HW is a multiple of 8, so the 8 columns of a lane stay inside one image.
+struct GeomBatchedBuf : GeomLinearBuf {
+    int HW, K, M;
+
+    __device__ __forceinline__ void init(long n)
+    {
+        xd = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(X), 0, (int)xbytes, GATHER_BUFFER_FLAGS);
+        ldx2 = (unsigned)HW * 2u;
+        ln2 = PAST_END;
+        if (n < N) {
+            const unsigned b = (unsigned)n / (unsigned)HW, hw = (unsigned)n - b * (unsigned)HW;
+            ln2 = (b * (unsigned)K * (unsigned)HW + hw) * 2u;
+        }
+    }
+
+    template <typename OutT, int CNT>
+    __device__ __forceinline__ void store(int row, long n, const OutT* vals) const
+    {
+        if (n < N) {
+            const unsigned b = (unsigned)n / (unsigned)HW, hw = (unsigned)n - b * (unsigned)HW;
+            OutT* p = static_cast<OutT*>(Y) + ((long)b * M + row) * HW + hw;
+            typedef OutT vec_t __attribute__((ext_vector_type(CNT)));
+            vec_t v;
+#pragma unroll
+            for (int e = 0; e < CNT; ++e) v[e] = vals[e];
+            __builtin_nontemporal_store(v, reinterpret_cast<vec_t*>(p));
+        }
+    }
+};
+
 // Convolution as implicit GEMM (Section 4.1): k = (c*R + r)*S + s, and
 // n = (b*Ho + y)*Wo + x for NCHW or n = (y*Wo + x)*B + b for CHWN.  This is
 // the general element-wise form; the unfolded matrix never exists in memory.
@@ -383,7 +417,7 @@ __global__ __launch_bounds__(64 * WAVES) void shflbw_gather_kernel(PackedView A,
     auto load_x = [&](const int (&c)[NLD], half8 (&x)[NLD], bool in_range) {
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
-            if constexpr (std::is_same<Geom, GeomLinearBuf>::value) x[i] = geom.load8(c[i], ln, !in_range);
+            if constexpr (std::is_base_of<GeomLinearBuf, Geom>::value) x[i] = geom.load8(c[i], ln, !in_range);
             else x[i] = geom.load8(in_range ? c[i] : -1, ln);
         }
     };

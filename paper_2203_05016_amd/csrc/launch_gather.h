@@ -13,9 +13,11 @@ int run_gather_f16(const shflbw_matrix* A, const GeomLinear<true>& g, long N, sh
 int run_gather_f16(const shflbw_matrix* A, const GeomLinearBuf& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_f16(const shflbw_matrix* A, const GeomLinear<false>& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_f16(const shflbw_matrix* A, const GeomConv& g, long N, shflbw_dtype ydtype, hipStream_t stream);
+int run_gather_f16(const shflbw_matrix* A, const GeomBatchedBuf& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_bf16(const shflbw_matrix* A, const GeomLinear<true>& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_bf16(const shflbw_matrix* A, const GeomLinearBuf& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_bf16(const shflbw_matrix* A, const GeomLinear<false>& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_bf16(const shflbw_matrix* A, const GeomConv& g, long N, shflbw_dtype ydtype, hipStream_t stream);
+int run_gather_bf16(const shflbw_matrix* A, const GeomBatchedBuf& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 
 }  // namespace shflbw

@@ -76,6 +76,23 @@ def test_conv_1x1_equals_spmm_path_bitwise():
     assert np.array_equal(got.reshape(64, 200).view(np.uint16), Y.cpu().numpy().view(np.uint16))
 
 
+@pytest.mark.parametrize("V,out_dtype", [(16, "float16"), (32, "float32"), (64, "float16"), (128, "float16")])
+def test_conv_1x1_nchw_one_launch_for_all_images(V, out_dtype):
+    """1x1, stride 1, no padding, NCHW with H*W a multiple of 8: one product per
+    image, all in one launch of the gather kernel (tiles of 64 columns span
+    several images of 24 positions here); against the oracle, and bit for
+    bit against the staged kernel on integers."""
+    announce("conv 1x1 nchw", V, out_dtype)
+    p = synth.make_conv(7, 40, 4, 6, 2 * V, 1, 1, V, 0.5, seed=241)
+    _parity(p, out_dtype=out_dtype)
+    q = synth.make_conv(7, 40, 4, 6, 2 * V, 1, 1, V, 0.5, seed=242, integer=True)
+    got = _run_conv(q, out_dtype="float32")
+    want, _ = c_oracle.conv2d(q.W, q.mask, q.conv["input"], 1, 1, (1, 1), (0, 0))
+    assert np.array_equal(got.astype(np.float64), want)
+    if V in (32, 64, 128):
+        assert np.array_equal(got, _run_conv(q, out_dtype="float32", kernel=2))
+
+
 @pytest.mark.parametrize("layout,batch,Cin,H,Wd,Cout,V", [
     ("NCHW", 2, 8, 6, 150, 32, 32),     # rows wider than a box: several boxes along x
     ("CHWN", 40, 8, 6, 50, 32, 32),     # batch innermost, boxes of a few positions x all images
