@@ -188,7 +188,7 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
  * positions can touch into LDS once and gathers from there; V = 16, and
  * inputs with too many channels for that, take the per-wave gather kernel.
  * A 1x1 convolution with unit stride and no padding is the linear-layer
- * product itself (CHWN: one matrix; NCHW with H*W a multiple of 8: one per
+ * product itself (CHWN: one matrix; NCHW with H*W a multiple of 4: one per
  * image, all in one launch) and runs as shflbw_spmm does.
  */
 int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out,

@@ -407,22 +407,32 @@ int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, 
     if (A->tune_kernel == 0 && layout == SHFLBW_CHWN && R == 1 && S == 1 && stride_h == 1 &&
         stride_w == 1 && pad_h == 0 && pad_w == 0)
         return shflbw_spmm(A, in, N, out, N, N, ydtype, stream);
-    // The same on NCHW tensors is one such product per image; with H*W a multiple of 8 the
-    // gather kernel takes all images in one launch (each lane's 8 columns stay inside an image),
+    // The same on NCHW tensors is one such product per image; with H*W a multiple of 4 the
+    // gather kernel takes all images in one launch (a lane's columns stay inside an image in
+    // runs of 8, or of 4),
     // reading only the channels a group keeps instead of staging every channel of a box.
     {
         const int64_t HW = (int64_t)H * W;
         const int64_t in_total = 2 * (int64_t)batch * C_in * HW;
         if (A->tune_kernel == 0 && layout == SHFLBW_NCHW && R == 1 && S == 1 && stride_h == 1 &&
-            stride_w == 1 && pad_h == 0 && pad_w == 0 && HW % 8 == 0 && HW * 2 < (1 << 24) &&
+            stride_w == 1 && pad_h == 0 && pad_w == 0 && HW % 4 == 0 && HW * 2 < (1 << 24) &&
             C_in < (1 << 24) && in_total < ((int64_t)1 << 32) - 64 &&
             reinterpret_cast<uintptr_t>(in) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0) {
-            GeomBatchedBuf g;
-            g.X = static_cast<const _Float16*>(in);
-            g.Y = out;
-            g.ldx = (long)HW; g.ldy = (long)HW; g.N = (long)N;
-            g.xbytes = (unsigned)in_total;
-            g.HW = (int)HW; g.K = C_in; g.M = A->M;
+            auto fill = [&](auto& g) {
+                g.X = static_cast<const _Float16*>(in);
+                g.Y = out;
+                g.ldx = (long)HW; g.ldy = (long)HW; g.N = (long)N;
+                g.xbytes = (unsigned)in_total;
+                g.HW = (int)HW; g.K = C_in; g.M = A->M;
+            };
+            if (HW % 8 == 0) {
+                GeomBatchedBuf g;
+                fill(g);
+                return dispatch_out(A, g, (long)N, ydtype, st);
+            }
+            // H*W a multiple of 4 only: every load and 8-wide store in two halves
+            GeomBatchedBuf4 g;
+            fill(g);
             return dispatch_out(A, g, (long)N, ydtype, st);
         }
     }

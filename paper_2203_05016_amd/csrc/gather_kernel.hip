@@ -226,6 +226,55 @@ struct GeomBatchedBuf : GeomLinearBuf {
     }
 };
 
+// The same for H*W a multiple of 4 only (14 x 14 images): a lane's 8 columns may cross
+// from one image into the next, but each half of 4 stays inside one, so every load and
+// every 8-wide store is done as two halves with an image base of their own.
+struct GeomBatchedBuf4 : GeomLinearBuf {
+    int HW, K, M;
+    unsigned ln2b;   // offset of the lane's columns 4..7
+
+    __device__ __forceinline__ unsigned image_offset(long n) const
+    {
+        if (n >= N) return PAST_END;
+        const unsigned b = (unsigned)n / (unsigned)HW, hw = (unsigned)n - b * (unsigned)HW;
+        return (b * (unsigned)K * (unsigned)HW + hw) * 2u;
+    }
+    __device__ __forceinline__ void init(long n)
+    {
+        xd = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(X), 0, (int)xbytes, GATHER_BUFFER_FLAGS);
+        ldx2 = (unsigned)HW * 2u;
+        ln2 = image_offset(n);
+        ln2b = image_offset(n + 4);
+    }
+    __device__ __forceinline__ half8 load8(int col, long, bool zero = false) const
+    {
+        typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+        typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+        const unsigned o = __umul24((unsigned)col, ldx2);
+        const bool none = col < 0 || zero;
+        const unsigned oa = (none || ln2 == PAST_END) ? PAST_END : o + ln2;
+        const unsigned ob = (none || ln2b == PAST_END) ? PAST_END : o + ln2b;
+        const uint2v lo = __builtin_amdgcn_raw_buffer_load_b64(xd, (int)oa, 0, 0);
+        const uint2v hi = __builtin_amdgcn_raw_buffer_load_b64(xd, (int)ob, 0, 0);
+        return __builtin_bit_cast(half8, uint4v{lo[0], lo[1], hi[0], hi[1]});
+    }
+    template <typename OutT, int CNT>
+    __device__ __forceinline__ void store(int row, long n, const OutT* vals) const
+    {
+        typedef OutT vec_t __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int h = 0; h < CNT / 4; ++h) {
+            const long nh = n + 4 * h;
+            if (nh < N) {
+                const unsigned b = (unsigned)nh / (unsigned)HW, hw = (unsigned)nh - b * (unsigned)HW;
+                OutT* p = static_cast<OutT*>(Y) + ((long)b * M + row) * HW + hw;
+                vec_t v = {vals[4 * h], vals[4 * h + 1], vals[4 * h + 2], vals[4 * h + 3]};
+                __builtin_nontemporal_store(v, reinterpret_cast<vec_t*>(p));
+            }
+        }
+    }
+};
+
 // Convolution as implicit GEMM (Section 4.1): k = (c*R + r)*S + s, and
 // n = (b*Ho + y)*Wo + x for NCHW or n = (y*Wo + x)*B + b for CHWN.  This is
 // the general element-wise form; the unfolded matrix never exists in memory.

@@ -14,10 +14,12 @@ int run_gather_f16(const shflbw_matrix* A, const GeomLinearBuf& g, long N, shflb
 int run_gather_f16(const shflbw_matrix* A, const GeomLinear<false>& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_f16(const shflbw_matrix* A, const GeomConv& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_f16(const shflbw_matrix* A, const GeomBatchedBuf& g, long N, shflbw_dtype ydtype, hipStream_t stream);
+int run_gather_f16(const shflbw_matrix* A, const GeomBatchedBuf4& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_bf16(const shflbw_matrix* A, const GeomLinear<true>& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_bf16(const shflbw_matrix* A, const GeomLinearBuf& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_bf16(const shflbw_matrix* A, const GeomLinear<false>& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_bf16(const shflbw_matrix* A, const GeomConv& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 int run_gather_bf16(const shflbw_matrix* A, const GeomBatchedBuf& g, long N, shflbw_dtype ydtype, hipStream_t stream);
+int run_gather_bf16(const shflbw_matrix* A, const GeomBatchedBuf4& g, long N, shflbw_dtype ydtype, hipStream_t stream);
 
 }  // namespace shflbw

@@ -91,6 +91,13 @@ def test_conv_1x1_nchw_one_launch_for_all_images(V, out_dtype):
     assert np.array_equal(got.astype(np.float64), want)
     if V in (32, 64, 128):
         assert np.array_equal(got, _run_conv(q, out_dtype="float32", kernel=2))
+    # H*W a multiple of 4 only (images of 14 x 14 and the like): loads and stores in halves
+    r = synth.make_conv(5, 40, 2, 6, 2 * V, 1, 1, V, 0.5, seed=243, integer=True)
+    for dt in ("float16", "float32"):
+        got = _run_conv(r, out_dtype=dt)
+        want, _ = c_oracle.conv2d(r.W, r.mask, r.conv["input"], 1, 1, (1, 1), (0, 0))
+        assert np.array_equal(got.astype(np.float64), want)
+    _parity(synth.make_conv(5, 40, 2, 6, 2 * V, 1, 1, V, 0.5, seed=244), out_dtype=out_dtype)
 
 
 @pytest.mark.parametrize("layout,batch,Cin,H,Wd,Cout,V", [
