@@ -154,3 +154,22 @@ def test_config4_resnet_conv_full():
     p = synth.config(3)
     _parity(p, kernel=2)
     _parity(p, kernel=1)
+
+
+def test_seeded_sweep_of_conv_geometries():
+    """Sixteen seeded draws of V, group count, batch, channels, image size,
+    1x1 / 3x3, stride, padding and layout, each against the oracle (few row
+    groups, so the shared-tile mapping and the 1x1 shortcuts are all hit)."""
+    rng = np.random.default_rng(2025)
+    for it in range(16):
+        V = int(rng.choice([32, 64, 128, 16]))
+        G = int(rng.integers(1, 6))
+        B = int(rng.integers(1, 6)); C = int(rng.integers(1, 40))
+        H = int(rng.integers(3, 20)); Wd = int(rng.integers(3, 20))
+        R = int(rng.choice([1, 3])); st = int(rng.choice([1, 2])); pad = int(rng.choice([0, 1]))
+        layout = str(rng.choice(["NCHW", "CHWN"]))
+        sp = float(rng.choice([0.0, 0.5, 0.75]))
+        announce("conv sweep", it, V, G, B, C, H, Wd, R, st, pad, layout, sp)
+        p = synth.make_conv(B, C, H, Wd, G * V, R, R, V, sp, seed=7000 + it, stride=(st, st),
+                            pad=(pad, pad), layout=layout)
+        _parity(p, out_dtype="float32")

@@ -331,3 +331,24 @@ def test_searched_pattern_end_to_end():
     Y = to_host(A.spmm(to_device(X)))
     Yr, S = c_oracle.spmm(W, mask, X)
     assert_within_scaled_tolerance(Y, Yr, S, what="searched pattern")
+
+
+def test_seeded_sweep_of_shapes_kernels_and_sparsities():
+    """Thirty seeded draws of V, group count, K, N (aligned and not), sparsity,
+    ragged kept counts, output type and kernel choice (automatic, gather,
+    split k-steps), each against the oracle."""
+    rng = np.random.default_rng(2024)
+    for it in range(30):
+        V = int(rng.choice([16, 32, 64, 128]))
+        G = int(rng.integers(1, 14))
+        K = int(rng.integers(1, 160)) * 8 if rng.random() < 0.8 else int(rng.integers(8, 900))
+        N = int(rng.integers(1, 60)) * 8 if rng.random() < 0.7 else int(rng.integers(1, 500))
+        sp = float(rng.choice([0.0, 0.3, 0.5, 0.75, 0.9, 0.97]))
+        kernel = int(rng.choice([0, 0, 1, 3]))
+        ragged = bool(rng.random() < 0.3)
+        out_dtype = str(rng.choice(["float16", "float32"]))
+        announce("sweep", it, V, G, K, N, sp, kernel, ragged, out_dtype)
+        p = synth.make_spmm(G * V, K, N, V, sp, seed=5000 + it, ragged=ragged)
+        Y = run_spmm(p, out_dtype=out_dtype, kernel=kernel)
+        Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+        assert_within_scaled_tolerance(Y, Yr, S, what="sweep case %d" % it)
