@@ -20,7 +20,8 @@
 //
 // When a block of 32 (or 64) tokens with all its features fits the LDS, a
 // second kernel keeps it there instead: every activation is read from HBM
-// once, the statistics come from the same loads (four tokens per wavefront),
+// once, the statistics come from the same loads (sixteen wavefronts, two or four
+// tokens each),
 // and the transposed rows are gathered from LDS columns, two neighbouring
 // features per lane (row pitch chosen so that the 64 four-byte reads of a
 // wavefront fall into 64 different banks).
@@ -234,7 +235,7 @@ __device__ __forceinline__ void ln_add_pair(unsigned w, float c, float& lo, floa
 }
 
 template <bool BF, int TOK, bool NORM>
-__global__ __launch_bounds__(16 * TOK) void layernorm_transpose_resident_kernel(LnArgs a, int P)
+__global__ __launch_bounds__(1024) void layernorm_transpose_resident_kernel(LnArgs a, int P)
 {
     extern __shared__ __attribute__((aligned(16))) char ln_smem[];
     uint16_t* xs = reinterpret_cast<uint16_t*>(ln_smem);                       // [TOK][P]
@@ -242,8 +243,8 @@ __global__ __launch_bounds__(16 * TOK) void layernorm_transpose_resident_kernel(
     float* st_rstd = st_mean + TOK;                                             // [TOK]
     float* gam = st_rstd + TOK;                                                 // [K]
     float* bet = gam + a.K;                                                     // [K]
-    constexpr int WAVES = TOK / 4;        // 8 or 16 wavefronts
-    constexpr int TPW = 4;                // tokens per wavefront
+    constexpr int WAVES = 16;
+    constexpr int TPW = TOK / WAVES;     // tokens per wavefront: 2 or 4
     constexpr int CH = TOK / 8;           // 16-byte token chunks per output row
     constexpr int FP = 64 / CH;           // feature pairs one wavefront stores per pass
     constexpr bool WIDE = (TOK == 32);    // its pitch keeps every row 8-byte aligned
@@ -653,7 +654,7 @@ extern "C" int shflbw_layernorm_transpose(const void* x, int64_t ldx, const void
             if (ea != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(ea));
             raised_on[which] = dev;
         }
-        hipLaunchKernelGGL(fn, dim3((unsigned)rwgs), dim3(16 * tok), bytes, st, a, pitch);
+        hipLaunchKernelGGL(fn, dim3((unsigned)rwgs), dim3(1024), bytes, st, a, pitch);
         hipError_t el = hipGetLastError();
         if (el != hipSuccess) return fail(SHFLBW_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(el));
         return SHFLBW_OK;
