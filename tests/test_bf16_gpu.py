@@ -98,6 +98,23 @@ def test_conv_both_kernels(layout, V):
                                            what="conv bf16 kernel %d" % kernel)
 
 
+@pytest.mark.parametrize("layout,H,Wd", [("NCHW", 4, 6), ("NCHW", 2, 6), ("CHWN", 3, 5)])
+def test_conv_1x1_shortcuts(layout, H, Wd):
+    """1x1, stride 1, no padding: the linear-layer product on CHWN tensors, one
+    launch over all images on NCHW tensors (H*W a multiple of 8, and of 4 only)."""
+    import torch
+    announce("bf16 conv 1x1", layout, H, Wd)
+    V = 32
+    p = synth.make_conv(7, 40, H, Wd, 2 * V, 1, 1, V, 0.5, seed=93, layout=layout, fmt="bf16")
+    g = p.conv
+    want, sc = c_oracle.conv2d(p.W, p.mask, g["input"], 1, 1, (1, 1), (0, 0), layout)
+    for dt, tol in ((torch.float32, 2.0 ** -10), (torch.bfloat16, TOL_BF16_OUT)):
+        A = binding.compress(p.W, p.mask, p.perm, V).bind_device("cuda:0")
+        out = A.conv2d(to_device(g["input"]), 1, 1, (1, 1), (0, 0), layout, out_dtype=dt)
+        torch.cuda.synchronize()
+        assert_within_scaled_tolerance(to_host(out), want, sc, tol=tol, what="conv 1x1 bf16")
+
+
 def test_output_type_must_match_operand_format():
     import torch
     announce("bf16 dtype checks")
