@@ -164,6 +164,44 @@ def measure_conv(p, steps, warmup, pairs=8):
     return dict(ms=ms, tflops=flop / (ms * 1e-3) / 1e12, flop=flop)
 
 
+def measure_conv_shapes(steps, warmup):
+    """ResNet-50-like layer shapes at batch 32, V = 32, 75 % sparsity, NCHW: this library's
+    conv2d on rotating input/output pairs, and the vendor's dense convolution as context."""
+    import torch
+    from paper_2203_05016_amd import binding, synth
+    shapes = [(64, 56, 64, 3, 1, 1), (128, 28, 128, 3, 1, 1), (256, 14, 256, 3, 1, 1), (512, 7, 512, 3, 1, 1),
+              (128, 56, 128, 3, 2, 1), (256, 56, 64, 1, 1, 0), (1024, 14, 256, 1, 1, 0), (2048, 7, 512, 1, 1, 0)]
+    res = {}
+    for (C, H, Co, R, st, pad) in shapes:
+        p = synth.make_conv(32, C, H, H, Co, R, R, 32, 0.75, seed=synth.BASE_SEED + 9000 + C + R,
+                            stride=(st, st), pad=(pad, pad))
+        g = p.conv
+        A = binding.compress(p.W, p.mask, p.perm, p.V).bind_device("cuda:0")
+        pairs = 4
+        xs = [torch.from_numpy(g["input"]).to("cuda:0") for _ in range(pairs)]
+        outs = [torch.empty((32, Co, g["Ho"], g["Wo"]), dtype=torch.float16, device="cuda:0") for _ in range(pairs)]
+        state = {"i": 0}
+
+        def fn():
+            j = state["i"] % pairs
+            A.conv2d(xs[j], R, R, (st, st), (pad, pad), "NCHW", out=outs[j])
+            state["i"] += 1
+        ms = time_steps(fn, steps, warmup)
+        wt = torch.from_numpy(p.W.reshape(Co, C, R, R)).to("cuda:0")
+
+        def dense():
+            j = state["i"] % pairs
+            torch.nn.functional.conv2d(xs[j], wt, stride=st, padding=pad)
+            state["i"] += 1
+        dense_ms = time_steps(dense, max(5, steps // 4), 3)
+        flop = 2.0 * A.info()["nnz"] * p.N
+        res["%dch_%dx%d_to_%dch_%dx%d_s%d" % (C, H, H, Co, R, R, st)] = dict(
+            ms=ms, tflops=flop / (ms * 1e-3) / 1e12, vendor_dense_conv_ms=dense_ms)
+        del xs, outs, wt
+        torch.cuda.empty_cache()
+    return res
+
+
 def measure_library_gemm(p, steps, warmup):
     """The vendor library's dense fp16 GEMM (torch.matmul) on the same shape,
     unpruned W, rotating operands: context for the speedup, not part of the path."""
@@ -358,6 +396,7 @@ def main():
             r = measure_spmm(q, args.steps, args.warmup, cold=True, graph=True)
             r1 = measure_spmm(q, args.steps, args.warmup, cold=True, kernel=1)
             extra["skinny_%dx%dx%d_s%.2f" % (M, K, N, sp)] = dict(r, whole_tile_gather_ms=r1["ms"])
+        extra["conv_shapes_batch32_V32_s0.75"] = measure_conv_shapes(50, 5)
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         with open(os.path.join(ROOT, "gpurun_out", "bench_all.json"), "w") as f:
             json.dump(extra, f, indent=1)
