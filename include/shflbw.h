@@ -28,9 +28,11 @@
  *    without synchronising.  Launch errors are returned; execution errors
  *    surface at the caller's next synchronisation.
  *  - Y / out are fully overwritten (no accumulate-into).
- *  - Activations and weights are IEEE binary16; products are accumulated in
- *    binary32 on the matrix cores; the result is rounded once to the
- *    requested output type.
+ *  - Activations and weights are 16-bit floating point, IEEE binary16 or
+ *    bfloat16 (one format per packed matrix, chosen at shflbw_compress);
+ *    products are accumulated in binary32 on the matrix cores; the result is
+ *    rounded once to the requested output type (the operands' format, or
+ *    binary32).
  */
 #ifndef SHFLBW_H
 #define SHFLBW_H
@@ -95,7 +97,8 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
  * unstructured pruning to the non-zero ratio beta gives a binary mask; K-Means with
  * clusters of the fixed size V on the rows of that mask groups the rows; vector-wise
  * pruning to the non-zero ratio alpha on the shuffled matrix; the shuffle is undone.
- *  W      host, M x K binary16 (SHFLBW_F16 only), finite, leading dimension ldw >= K.
+ *  W      host, M x K of wdtype (SHFLBW_F16 or SHFLBW_BF16), finite, leading dimension
+ *         ldw >= K.  V must be 16, 32, 64 or 128 and divide M.
  *  alpha  target non-zero ratio in [0, 1]: every group keeps round(alpha*K) vectors.
  *  beta   ratio of the unstructured step; negative = 2*alpha (capped at 1), the value
  *         the paper recommends.
@@ -105,6 +108,10 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
  *  mask_out  M x K bytes (leading dimension K), original row order; conforms to the
  *         pattern under perm_out.
  * Deterministic: comparisons are exact and ties go to the lower index.
+ * Cost: a K-Means round compares every row with every cluster centre, O(M * (M/V) * K)
+ * byte operations, and holds 12 bytes per (row, cluster) pair; the unstructured step holds
+ * 4 bytes per weight.  Flat indices are 32-bit: M*K or M*(M/V) above 2^32 - 1 is refused
+ * with SHFLBW_ERR_BAD_SHAPE.
  */
 int shflbw_pattern_search(const void* W, int ldw, int M, int K, int V, double alpha, double beta,
                           int iterations, shflbw_dtype wdtype, int32_t* perm_out, uint8_t* mask_out);
@@ -218,6 +225,12 @@ int shflbw_layernorm_transpose(const void* x, int64_t ldx, const void* gamma, co
 
 const char* shflbw_status_string(int status);
 const char* shflbw_last_error(void); /* thread-local, never NULL */
+
+/* Which kernel the calling thread's most recent successful shflbw_spmm or shflbw_conv2d
+ * launched, as "name<template arguments>" (the automatic choice of set_tuning(0, 0) is
+ * made per call from the matrix and the operand shape).  Thread-local, never NULL; empty
+ * before the first launch. */
+const char* shflbw_last_kernel(void);
 
 #ifdef __cplusplus
 }

@@ -23,7 +23,7 @@ EXPORTS = [
     "shflbw_compress", "shflbw_pattern_search", "shflbw_destroy", "shflbw_info", "shflbw_row_indices",
     "shflbw_group_columns", "shflbw_decompress", "shflbw_device_bytes", "shflbw_bind_device",
     "shflbw_set_tuning", "shflbw_device_status", "shflbw_set_wait_limit", "shflbw_spmm", "shflbw_conv2d",
-    "shflbw_layernorm_transpose", "shflbw_status_string", "shflbw_last_error",
+    "shflbw_layernorm_transpose", "shflbw_status_string", "shflbw_last_error", "shflbw_last_kernel",
 ]
 
 
@@ -78,6 +78,8 @@ def lib():
         L.shflbw_status_string.argtypes = [i32]
         L.shflbw_last_error.restype = ctypes.c_char_p
         L.shflbw_last_error.argtypes = []
+        L.shflbw_last_kernel.restype = ctypes.c_char_p
+        L.shflbw_last_kernel.argtypes = []
         _lib = L
     return _lib
 
@@ -88,6 +90,11 @@ def status_string(status):
 
 def last_error():
     return lib().shflbw_last_error().decode()
+
+
+def last_kernel():
+    """Name of the kernel this thread's last spmm / conv2d call launched."""
+    return lib().shflbw_last_kernel().decode()
 
 
 def _check(rc):
@@ -194,16 +201,43 @@ class Matrix:
         self._dev = buf
         return self
 
+    def _require_on_bound_device(self, t, what):
+        """The C ABI takes bare addresses: it cannot tell a host tensor, or one on
+        another GPU, from device memory of the GPU the matrix is bound to."""
+        if self._dev is None:
+            raise RuntimeError("call bind_device before %s" % what)
+        if not t.is_cuda or t.device != self._dev.device:
+            raise ValueError("%s must live on %s, where the matrix is bound (got %s)"
+                             % (what, self._dev.device, t.device))
+
     def spmm(self, X, Y=None, out_dtype=None, stream=None):
         """Y = (W . mask) X for a device tensor X of shape (K, N) in the
-        matrix's operand format (float16, or bfloat16)."""
+        matrix's operand format (float16, or bfloat16).  The C ABI has no K
+        argument and sees only addresses, so shapes, strides and devices are
+        checked here, before anything is enqueued."""
         if X.dtype != self._operand_dtype() or X.dim() != 2 or X.stride(1) != 1 and X.shape[1] > 1:
             raise TypeError("X must be a 2-D %s tensor with unit column stride" % self._operand_dtype())
+        info = self.info()
         K, N = X.shape
+        if K != info["K"]:
+            raise ValueError("X has %d rows, the packed matrix has K = %d columns" % (K, info["K"]))
+        if K > 1 and X.stride(0) < N:
+            raise ValueError("rows of X overlap (row stride %d < N = %d)" % (X.stride(0), N))
+        if Y is not None:
+            if Y.dim() != 2 or tuple(Y.shape) != (info["M"], N):
+                raise ValueError("Y must have shape (%d, %d), got %r" % (info["M"], N, tuple(Y.shape)))
+            if N > 1 and Y.stride(1) != 1:
+                raise ValueError("Y must have unit column stride")
+            if Y.shape[0] > 1 and Y.stride(0) < N:
+                raise ValueError("rows of Y overlap (row stride %d < N = %d)" % (Y.stride(0), N))
+            _ydtype(Y)
+        self._require_on_bound_device(X, "X")
         if Y is None:
             import torch
-            Y = torch.empty((self.info()["M"], N), dtype=out_dtype or self._operand_dtype(),
+            Y = torch.empty((info["M"], N), dtype=out_dtype or self._operand_dtype(),
                             device=X.device)
+        else:
+            self._require_on_bound_device(Y, "Y")
         ldx = X.stride(0) if K > 1 else max(N, 1)
         ldy = Y.stride(0) if Y.shape[0] > 1 else max(N, 1)
         rc = lib().shflbw_spmm(self._h, X.data_ptr(), ldx, Y.data_ptr(), ldy, N, _ydtype(Y),
@@ -216,18 +250,32 @@ class Matrix:
                out_dtype=None, stream=None):
         """Masked conv2d of a contiguous device tensor in the matrix's operand format."""
         import torch
-        if inp.dtype != self._operand_dtype() or not inp.is_contiguous():
-            raise TypeError("input must be a contiguous %s tensor" % self._operand_dtype())
+        if inp.dtype != self._operand_dtype() or not inp.is_contiguous() or inp.dim() != 4:
+            raise TypeError("input must be a contiguous 4-D %s tensor" % self._operand_dtype())
+        if layout not in ("NCHW", "CHWN"):
+            raise ValueError("layout must be 'NCHW' or 'CHWN'")
         if layout == "NCHW":
             B, C, H, W = inp.shape
         else:
             C, H, W, B = inp.shape
+        info = self.info()
+        if C * R * S != info["K"]:
+            raise ValueError("C_in*R*S = %d does not match the packed matrix's K = %d" % (C * R * S, info["K"]))
+        if min(stride) < 1 or min(pad) < 0 or H + 2 * pad[0] < R or W + 2 * pad[1] < S:
+            raise ValueError("bad stride, padding or kernel size")
         Ho = (H + 2 * pad[0] - R) // stride[0] + 1
         Wo = (W + 2 * pad[1] - S) // stride[1] + 1
+        Cout = info["M"]
+        shape = (B, Cout, Ho, Wo) if layout == "NCHW" else (Cout, Ho, Wo, B)
+        if out is not None:
+            if tuple(out.shape) != shape or not out.is_contiguous():
+                raise ValueError("out must be a contiguous tensor of shape %r, got %r" % (shape, tuple(out.shape)))
+            _ydtype(out)
+        self._require_on_bound_device(inp, "input")
         if out is None:
-            Cout = self.info()["M"]
-            shape = (B, Cout, Ho, Wo) if layout == "NCHW" else (Cout, Ho, Wo, B)
             out = torch.empty(shape, dtype=out_dtype or self._operand_dtype(), device=inp.device)
+        else:
+            self._require_on_bound_device(out, "out")
         _check(lib().shflbw_conv2d(self._h, inp.data_ptr(), out.data_ptr(), B, C, H, W, R, S,
                                    stride[0], stride[1], pad[0], pad[1],
                                    NCHW if layout == "NCHW" else CHWN, _ydtype(out),
@@ -273,6 +321,11 @@ def layernorm_transpose(x, gamma=None, beta=None, eps=1e-5, normalize=True, out=
         out = torch.empty((K, N), dtype=x.dtype, device=x.device)
     if out.dtype != x.dtype or out.shape != (K, N) or out.stride(1) != 1:
         raise TypeError("out must be a (K, N) tensor of x's dtype with unit token stride")
+    for t in (x, out, gamma, beta):
+        if t is not None and (not t.is_cuda or t.device != x.device):
+            raise ValueError("x, gamma, beta and out must live on one GPU")
+    if (N > 1 and x.stride(0) < K) or (K > 1 and out.stride(0) < N):
+        raise ValueError("rows of x or out overlap")
     ptr = lambda t: ctypes.c_void_p(None if t is None else t.data_ptr())
     _check(lib().shflbw_layernorm_transpose(ptr(x), x.stride(0) if N > 1 else K, ptr(gamma), ptr(beta),
                                             float(eps), 1 if normalize else 0, ptr(out),
@@ -283,15 +336,17 @@ def layernorm_transpose(x, gamma=None, beta=None, eps=1e-5, normalize=True, out=
 
 
 def pattern_search(W, V, alpha, beta=None, iterations=10):
-    """shflbw_pattern_search on a numpy float16 matrix: returns (perm, mask)
-    ready for ``compress``.  beta None = the paper's 2*alpha."""
-    if W.dtype != np.float16 or W.ndim != 2:
-        raise TypeError("W must be a 2-D float16 array")
+    """shflbw_pattern_search on a numpy matrix (float16, or uint16 holding
+    bfloat16 bit patterns): returns (perm, mask) ready for ``compress``.
+    beta None = the paper's 2*alpha."""
+    if W.dtype not in (np.float16, np.uint16) or W.ndim != 2:
+        raise TypeError("W must be a 2-D float16 array, or uint16 holding bfloat16 bits")
     W = np.ascontiguousarray(W)
     M, K = W.shape
     perm = np.empty(M, dtype=np.int32)
     mask = np.empty((M, K), dtype=np.uint8)
     _check(lib().shflbw_pattern_search(_host_ptr(W), K, M, K, V, float(alpha),
-                                       -1.0 if beta is None else float(beta), int(iterations), F16,
+                                       -1.0 if beta is None else float(beta), int(iterations),
+                                       BF16 if W.dtype == np.uint16 else F16,
                                        _host_ptr(perm), _host_ptr(mask)))
     return perm, mask

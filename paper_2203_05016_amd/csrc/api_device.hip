@@ -20,6 +20,15 @@ int hip_fail(hipError_t e, const char* what)
     return fail(SHFLBW_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
+// "name<V,second,operand format,output format>" for shflbw_last_kernel
+std::string kernel_name(const char* base, int V, int second, bool f32_out, bool bf)
+{
+    char buf[128];
+    snprintf(buf, sizeof buf, "%s<%d,%d,%s,%s>", base, V, second, bf ? "bf16" : "f16",
+             f32_out ? "f32 out" : (bf ? "bf16 out" : "f16 out"));
+    return buf;
+}
+
 PackedView view_of(const shflbw_matrix* A)
 {
     const char* b = static_cast<const char*>(A->dev_base);
@@ -55,6 +64,7 @@ int launch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long l
                        stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    note_kernel(kernel_name("shflbw_slab_kernel", V, GW, sizeof(OutT) == 4, BF));
     return SHFLBW_OK;
 }
 
@@ -208,6 +218,7 @@ int launch_conv_nt(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStr
                        stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    note_kernel(kernel_name("shflbw_conv_kernel", V, NT, sizeof(OutT) == 4, BF));
     return SHFLBW_OK;
 }
 

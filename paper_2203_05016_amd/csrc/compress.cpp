@@ -12,6 +12,7 @@
 
 namespace {
 thread_local std::string g_last_error;
+thread_local std::string g_last_kernel;
 
 // Position of (stored row i of the group, step column j) inside one k-step's
 // V*TK values; see the layout comment in shflbw_internal.h.
@@ -71,11 +72,13 @@ int fail(int status, const std::string& detail)
     g_last_error = detail;
     return status;
 }
+void note_kernel(const std::string& name) { g_last_kernel = name; }
 }  // namespace shflbw
 
 extern "C" {
 
 const char* shflbw_last_error(void) { return g_last_error.c_str(); }
+const char* shflbw_last_kernel(void) { return g_last_kernel.c_str(); }
 
 const char* shflbw_status_string(int status)
 {

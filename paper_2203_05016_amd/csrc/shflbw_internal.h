@@ -92,6 +92,7 @@ static_assert((SLAB_ZERO_ROW + 1) * SLAB_ROW_BYTES / 16 <= (1 << 13), "LDS offse
 // different bank groups; bit 1 varies with the next row bit.
 constexpr int slab_swizzle(int r) { return ((r & 3) << 2) | (((r >> 2) & 1) << 1); }
 int fail(int status, const std::string& detail);  // records the thread-local text, returns status
+void note_kernel(const std::string& name);        // records what the calling thread launched last (shflbw_last_kernel)
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 }  // namespace shflbw
 

@@ -71,20 +71,90 @@ def test_kmeans_keeps_every_cluster_at_v_rows_and_is_deterministic():
     assert np.array_equal(a, pattern_search.balanced_kmeans(B.copy(), 5, 6))
 
 
+def test_unstructured_step_keeps_exactly_the_largest_magnitudes_ties_to_the_lower_index():
+    """Direct pin of the unstructured step: the count is round(beta M K) with halves
+    rounded up, no dropped weight is larger in magnitude than a kept one, and among
+    weights at the threshold magnitude the kept ones are those with the lowest
+    flat indices.  Checked with plain Python on values that tie heavily."""
+    rng = np.random.default_rng(806)
+    for (M, K, beta) in ((6, 10, 0.3), (5, 7, 0.5), (4, 9, 0.125), (3, 5, 0.1), (7, 3, 1.0), (7, 3, 0.0)):
+        W = rng.integers(-3, 4, size=(M, K)).astype(np.float16)     # seven magnitudes: many ties
+        W[0, 0] = np.float16(-0.0)
+        B = pattern_search.unstructured_mask(W, beta)
+        flat = [abs(float(v)) for v in W.reshape(-1)]
+        kept = [i for i, b in enumerate(B.reshape(-1)) if b]
+        dropped = [i for i, b in enumerate(B.reshape(-1)) if not b]
+        want = int(beta * M * K + 0.5)                                # 17.5 -> 18, 4.5 -> 5, 1.5 -> 2
+        assert len(kept) == want, (M, K, beta)
+        if kept and dropped:
+            thr = min(flat[i] for i in kept)
+            assert thr >= max(flat[i] for i in dropped)
+            at_thr_kept = [i for i in kept if flat[i] == thr]
+            at_thr_dropped = [i for i in dropped if flat[i] == thr]
+            if at_thr_dropped:
+                assert max(at_thr_kept) < min(at_thr_dropped)
+    # the same on bfloat16 bit patterns (sign bit ignored, magnitudes by their bits)
+    Wb = synth.float32_to_bfloat16_bits(np.array([[1.0, -2.0, 0.5, 2.0], [-0.5, 3.0, -3.0, 0.25]], dtype=np.float32))
+    assert pattern_search.unstructured_mask(Wb, 0.5).tolist() == [[0, 1, 0, 1], [0, 1, 1, 0]]
+
+
+def test_kmeans_hand_worked_four_rows():
+    """Four rows, two clusters of two, worked by hand.  Rows: r0 = r2 = 1100, r1 = 0011,
+    r3 = 0010; start {r0, r1}, {r2, r3}.  Column counts n0 = 1111, n1 = 1110; with
+    V^2 |b - c|^2 = sum_k (2 b_k - n_k)^2 the distances are r0: 4, 3; r1: 4, 7; r2: 4, 3;
+    r3: 4, 3.  Going through the pairs by distance, then row, then cluster: (r0, c1) and
+    (r2, c1) fill cluster 1, r3 finds it full, and the distance-4 pairs put r1 and r3 into
+    cluster 0: assignment 1, 0, 1, 0.  Second round: n0 = 0021, n1 = 2200, distances r0: 13, 0;
+    r1: 1, 16; r2: 13, 0; r3: 1, 12 - nothing moves, the search stops."""
+    B = np.array([[1, 1, 0, 0], [0, 0, 1, 1], [1, 1, 0, 0], [0, 0, 1, 0]], dtype=np.int64)
+    assert pattern_search.balanced_kmeans(B, 2, 0).tolist() == [0, 0, 1, 1]
+    assert pattern_search.balanced_kmeans(B, 2, 1).tolist() == [1, 0, 1, 0]
+    assert pattern_search.balanced_kmeans(B, 2, 10).tolist() == [1, 0, 1, 0]
+    # the whole search on weights with that mask: groups {r1, r3} and {r0, r2}, each keeps its
+    # two heaviest columns (r1 + r3: columns 2 and 3; r0 + r2: columns 0 and 1)
+    W = np.array([[4, 3, .1, .1], [.1, .1, 5, 2], [3, 4, .1, .1], [.1, .2, 6, .3]], dtype=np.float16)
+    perm, mask = pattern_search.search(W, 2, alpha=0.5, beta=7 / 16, iterations=5)
+    assert perm.tolist() == [1, 3, 0, 2]
+    assert mask.tolist() == [[1, 1, 0, 0], [0, 0, 1, 1], [1, 1, 0, 0], [0, 0, 1, 1]]
+
+
+def test_bfloat16_vector_scores_are_exact_sums():
+    """A vector's score is the exact sum of its magnitudes: compared here with rational
+    arithmetic on values whose exponents lie 60 binary orders apart, where a
+    floating-point sum would lose the small terms."""
+    from fractions import Fraction
+    vals = np.array([[2.0 ** 40, 2.0 ** 40], [2.0 ** -20, 0.0], [1.5, 1.5], [0.0, 2.0 ** -21]], dtype=np.float32)
+    bits = synth.float32_to_bfloat16_bits(vals)
+    mag = pattern_search.exact_magnitude(bits)
+    want = [sum(Fraction(float(v)) for v in np.abs(vals[:, k])) * Fraction(2) ** 133 for k in range(2)]
+    assert [int(mag[:, k].sum()) for k in range(2)] == [int(w) for w in want]
+    assert want[0] > want[1]                      # decided by 2^-20 against 2^-21, far below 2^40's last bit
+    perm, mask = pattern_search.search(bits, 4, alpha=0.5, iterations=0)
+    assert mask[:, 0].all() and not mask[:, 1].any()
+    # a subnormal and the smallest normal
+    tiny = np.array([[0x0001, 0x0080]], dtype=np.uint16)
+    assert pattern_search.exact_magnitude(tiny).tolist() == [[1, 128]]
+
+
 # ----------------------------------------------------------------- the library against the oracle
 from paper_2203_05016_amd import binding
 
 
+@pytest.mark.parametrize("fmt", ["f16", "bf16"])
 @pytest.mark.parametrize("M,K,V,alpha,beta,its", [
-    (64, 96, 8, 0.25, None, 10), (48, 64, 4, 0.125, 0.125, 10), (128, 200, 32, 0.1, None, 4),
-    (32, 40, 16, 0.5, 1.0, 3), (12, 40, 1, 0.25, None, 3), (12, 40, 4, 0.25, None, 0),
-    (64, 72, 8, 0.0, None, 2), (64, 72, 8, 1.0, None, 2),
+    (64, 96, 16, 0.25, None, 10), (128, 64, 16, 0.125, 0.125, 10), (128, 200, 32, 0.1, None, 4),
+    (32, 40, 16, 0.5, 1.0, 3), (128, 40, 64, 0.25, None, 3), (48, 40, 16, 0.25, None, 0),
+    (64, 72, 16, 0.0, None, 2), (64, 72, 32, 1.0, None, 2), (256, 24, 128, 0.3, None, 3),
+    (48, 7, 16, 0.5, 0.5, 4),
 ])
-def test_library_search_equals_the_oracle_bit_for_bit(M, K, V, alpha, beta, its):
+def test_library_search_equals_the_oracle_bit_for_bit(M, K, V, alpha, beta, its, fmt):
     rng = np.random.Generator(np.random.PCG64(810 + M + K + V))
-    W = rng.standard_normal((M, K), dtype=np.float32).astype(np.float16)
+    W = rng.standard_normal((M, K), dtype=np.float32)
+    if fmt == "bf16":
+        W *= np.exp2(rng.integers(-30, 30, size=(M, 1))).astype(np.float32)   # rows of very different scale
     W[rng.random((M, K)) < 0.05] = 0            # ties among zeros
     W[0, :5] = W[1, :5]                          # ties among equal magnitudes
+    W = W.astype(np.float16) if fmt == "f16" else synth.float32_to_bfloat16_bits(W)
     perm, mask = binding.pattern_search(W, V, alpha, beta, its)
     perm_o, mask_o = pattern_search.search(W, V, alpha, beta, its)
     assert np.array_equal(perm, perm_o)
@@ -92,8 +162,8 @@ def test_library_search_equals_the_oracle_bit_for_bit(M, K, V, alpha, beta, its)
 
 
 def test_library_search_on_planted_groups_and_into_compress():
-    W, truth, _ = _planted(96, 128, 8, 16, seed=811)
-    perm, mask = binding.pattern_search(W, 8, 16 / 128, 16 / 128, 10)
+    W, truth, _ = _planted(96, 128, 16, 16, seed=811)
+    perm, mask = binding.pattern_search(W, 16, 16 / 128, 16 / 128, 10)
     assert np.array_equal(mask, truth)
     W2, truth2, _ = _planted(128, 160, 16, 24, seed=812)
     perm2, mask2 = binding.pattern_search(W2, 16, 24 / 160, 24 / 160, 10)
@@ -105,10 +175,34 @@ def test_library_search_on_planted_groups_and_into_compress():
 
 def test_library_search_argument_checks():
     W = np.zeros((8, 8), dtype=np.float16)
+    W = np.zeros((64, 8), dtype=np.float16)
+    for V in (3, 4, 8, 0, -16, 256):                    # only the group sizes the packed format has
+        with pytest.raises(binding.ShflbwError) as e:
+            binding.pattern_search(W, V, 0.5)
+        assert e.value.status == -2
     with pytest.raises(binding.ShflbwError):
-        binding.pattern_search(W, 3, 0.5)               # M % V != 0
+        binding.pattern_search(np.zeros((40, 8), dtype=np.float16), 16, 0.5)   # M % V != 0
     with pytest.raises(binding.ShflbwError):
-        binding.pattern_search(W, 4, 1.5)               # alpha outside [0, 1]
+        binding.pattern_search(W, 16, 1.5)              # alpha outside [0, 1]
     W[0, 0] = np.inf
     with pytest.raises(binding.ShflbwError):
-        binding.pattern_search(W, 4, 0.5)               # non-finite weight
+        binding.pattern_search(W, 16, 0.5)              # non-finite weight
+    Wb = np.zeros((64, 8), dtype=np.uint16)
+    Wb[3, 3] = 0x7F80                                   # bfloat16 infinity
+    with pytest.raises(binding.ShflbwError):
+        binding.pattern_search(Wb, 16, 0.5)
+
+
+def test_library_search_refuses_shapes_beyond_32_bit_indices():
+    """M*K and M*(M/V) index weights and (row, cluster) pairs with 32 bits; larger
+    shapes are refused before anything is read (the pointers are never touched)."""
+    import ctypes
+    L = binding.lib()
+    one = np.zeros(1, dtype=np.float16)
+    perm = np.zeros(1, dtype=np.int32)
+    mask = np.zeros(1, dtype=np.uint8)
+    ptr = lambda a: ctypes.c_void_p(a.ctypes.data)
+    for (M, K, V) in ((1 << 16, 1 << 16, 16), (1 << 20, 4096, 16), (1 << 19, 8, 16)):
+        rc = L.shflbw_pattern_search(ptr(one), K, M, K, V, 0.5, -1.0, 1, binding.F16, ptr(perm), ptr(mask))
+        assert rc == -2, (M, K, V)
+        assert "2^32" in binding.last_error()
