@@ -27,10 +27,14 @@ sys.path.insert(0, ROOT)
 
 MFMA_F16_PEAK = 2.5166e15      # 256 CU x 4096 FLOP/clk x 2.4 GHz
 HBM_PEAK = 8.0e12
-L2_TO_CU_BYTES = 334.0e6        # 2.609e6 read requests of 128 B per launch of the headline kernel
-# HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# scaled by the same counters on a 64 MiB copy (profiles/slab_kernel_ffn_config2_pmc.md)
-MEASURED_TRAFFIC_BYTES = 109.2e6
+# Counter readings of the headline kernel, copied from the rocprofv3 --pmc summary named in
+# COUNTER_SOURCE (they are not measured by this run: counters are collected in runs of their
+# own).  They are reported only when the run launches what that summary profiled: automatic
+# kernel choice, no tile override, and the kernel named in COUNTER_KERNEL.
+COUNTER_SOURCE = "profiles/slab_kernel_ffn_config2_pmc.md"
+COUNTER_KERNEL = "shflbw_slab_kernel<32,12,f16,f16 out>"
+L2_TO_CU_BYTES = 334.0e6        # TCP_TCC_READ_REQ x 128 B per launch
+MEASURED_TRAFFIC_BYTES = 109.2e6  # FETCH_SIZE + WRITE_SIZE per launch, scaled by the same counters on a 64 MiB copy
 PAPER_CONTEXT = "paper: up to 1.81x/4.18x/1.90x over cuBLAS dense at 75% on V100/T4/A100 (context only)"
 
 
@@ -125,15 +129,21 @@ def rotation_for(p, out_bytes=2, cache=256 << 20):
     return max(2, min(8, -(-2 * cache // per)))
 
 
-def measure_spmm(p, steps, warmup, cold=True, graph=False, **kw):
+def measure_spmm(p, steps, warmup, cold=True, graph=False, sample_rows=None, **kw):
+    """Times `steps` launches.  sample_rows: row indices whose results, as the timed launches
+    left them in every rotating output buffer, are returned for the check against the oracle."""
     import torch
+    from paper_2203_05016_amd import binding
     rot = rotation_for(p) if cold else 1
     c = Case(p, rot, **kw)
     ms = time_steps(c.step, steps, warmup)
     c.A.device_status()   # raises if a bounded hand-over wait ran out in any of these launches
     r = dict(ms=ms, tflops=c.flop() / (ms * 1e-3) / 1e12, gbps=c.bytes() / (ms * 1e-3) / 1e9,
              nnz=c.info["nnz"], sparsity=c.info["sparsity"], bytes=c.bytes(), flop=c.flop(),
-             rotate=rot)
+             rotate=rot, kernel=binding.last_kernel())
+    if sample_rows is not None:
+        idx = torch.as_tensor(np.asarray(sample_rows), device="cuda:0")
+        r["sample"] = [y.index_select(0, idx).float().cpu().numpy() for y in c.Y[:min(rot, steps + warmup)]]
     if graph:
         # the same launches, rotating operands included, replayed from a HIP graph
         r["graph_ms"] = time_graph(c.step, 4 * rot, max(1, steps // (4 * rot)))
@@ -243,14 +253,29 @@ def measure_layernorm_transpose(p, steps, warmup):
     return dict(ms=ms, bytes=nbytes, GBps=nbytes / (ms * 1e-3) / 1e9, hbm_frac=nbytes / (ms * 1e-3) / HBM_PEAK)
 
 
+PROBE_SRC = os.path.join(ROOT, "bench_l2_probe.hip")
+PROBE_LIB = os.path.join(ROOT, "bench_l2_probe.so")
+
+
+def build_probe():
+    """Compile the L2 streaming probe (measurement aid, not part of the product)."""
+    import subprocess
+    from paper_2203_05016_amd import build as lib_build
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = PROBE_LIB + ".tmp.%d" % os.getpid()
+    subprocess.check_call([hipcc, "-x", "hip", PROBE_SRC, "-shared", "-o", tmp] + lib_build.FLAGS,
+                          stderr=subprocess.DEVNULL)
+    os.replace(tmp, PROBE_LIB)
+    return PROBE_LIB
+
+
 def measure_l2_stream(p):
     """The probe library's two streaming runs on the headline's X: the rate at which the
     L2s can feed LDS with this access pattern when nothing else runs (hot), and with the
     slab kernel's grid and sharing on cold operands."""
     import ctypes
     import torch
-    path = os.path.join(ROOT, "paper_2203_05016_amd", "libshflbw_probe.so")
-    lib = ctypes.CDLL(path)
+    lib = ctypes.CDLL(PROBE_LIB if os.path.exists(PROBE_LIB) else build_probe())
     fn = lib.shflbw_probe_l2_stream
     fn.restype = ctypes.c_longlong
     fn.argtypes = [ctypes.c_void_p, ctypes.c_longlong, ctypes.c_int, ctypes.c_longlong, ctypes.c_int,
@@ -272,6 +297,21 @@ def measure_l2_stream(p):
         ms = time_steps(step, steps, 5)
         out[name] = {"ms": ms, "bytes": state["bytes"], "GBps": state["bytes"] / (ms * 1e-3) / 1e9}
     return out
+
+
+def check_sample(p, rows, samples):
+    """The rows `rows` of every output buffer the timed launches wrote, against the oracle
+    (element-wise, the parity tests' bound)."""
+    from oracle import c_oracle
+    Yr, S = c_oracle.spmm(np.ascontiguousarray(p.W[rows]), np.ascontiguousarray(p.mask[rows]), p.X)
+    worst = 0.0
+    for y in samples:
+        err = np.abs(y.astype(np.float64) - Yr)
+        ok_zero = bool(np.all(y[S == 0] == 0))
+        ratio = float(np.max(np.where(S > 0, err / np.where(S > 0, S, 1.0), 0.0)))
+        worst = max(worst, ratio if ok_zero and np.all(np.isfinite(y)) else float("inf"))
+    return {"rows_checked": int(len(rows)), "buffers_checked": len(samples), "max_scaled_error": worst,
+            "bound": 2.0 ** -10, "ok": bool(worst <= 2.0 ** -10)}
 
 
 def cpu_baseline(p):
@@ -341,7 +381,10 @@ def main():
         print(json.dumps({"pmc_run": True, "workload": args.pmc_workload,
                           "copy_bytes_each_way": 64 << 20, "launches": 3}))
         return
-    main_r = measure_spmm(p, args.steps, args.warmup, cold=True, tile_n=args.tile_n, kernel=args.kernel)
+    check_rows = np.sort(np.random.Generator(np.random.PCG64(77)).choice(p.M, 24, replace=False))
+    main_r = measure_spmm(p, args.steps, args.warmup, cold=True, tile_n=args.tile_n, kernel=args.kernel,
+                          sample_rows=check_rows)
+    main_sample = main_r.pop("sample")
     if args.headline_only:
         achieved = main_r["bytes"] / (main_r["ms"] * 1e-3)
         print(json.dumps({"metric": "useful TFLOP/s (2*nnz*N/s), Shfl-BW SpMM at 75% sparsity, V=32",
@@ -352,12 +395,14 @@ def main():
         return
     warm_r = measure_spmm(p, args.steps, args.warmup, cold=False, tile_n=args.tile_n, kernel=args.kernel)
     dense_p = synth.config(1, sparsity=0.0)
-    dense_r = measure_spmm(dense_p, max(10, args.steps // 4), max(3, args.warmup // 4), cold=True,
-                           tile_n=args.tile_n, kernel=args.kernel)
+    # the two legs of the speedup are timed alike: same steps, same warm-up, same rotation rule
+    dense_r = measure_spmm(dense_p, args.steps, args.warmup, cold=True,
+                           tile_n=args.tile_n, kernel=args.kernel, sample_rows=check_rows)
+    dense_sample = dense_r.pop("sample")
     ident_p = synth.config(1, identity_perm=True)
     ident_r = measure_spmm(ident_p, args.steps, args.warmup, cold=True, tile_n=args.tile_n, kernel=args.kernel)
     conv_r = measure_conv(synth.config(3), args.steps, args.warmup)
-    conv_dense = measure_conv(synth.config(3, sparsity=0.0), max(10, args.steps // 4), max(3, args.warmup // 4))
+    conv_dense = measure_conv(synth.config(3, sparsity=0.0), args.steps, args.warmup)
     conv_r["speedup_vs_own_dense"] = conv_dense["ms"] / conv_r["ms"]
     conv_r["dense_ms"] = conv_dense["ms"]
     bf16_r = measure_spmm(synth.config(1, fmt="bf16"), args.steps, args.warmup, cold=True,
@@ -367,9 +412,12 @@ def main():
     l2_r = measure_l2_stream(p)
     # bytes the headline kernel pulls from the L2s into its CUs per launch (TCP_TCC_READ_REQ x 128 B,
     # profiles/slab_kernel_ffn_config2_pmc.md) over its launch time, against the probe's rates
-    l2_r["kernel_l2_bytes_per_launch"] = L2_TO_CU_BYTES
-    l2_r["kernel_l2_GBps"] = L2_TO_CU_BYTES / (main_r["ms"] * 1e-3) / 1e9
-    l2_r["frac_of_hot_stream"] = l2_r["kernel_l2_GBps"] / l2_r["hot"]["GBps"]
+    counters_apply = args.kernel == 0 and args.tile_n == 0 and main_r["kernel"] == COUNTER_KERNEL
+    if counters_apply:
+        l2_r["kernel_l2_bytes_per_launch"] = L2_TO_CU_BYTES
+        l2_r["kernel_l2_bytes_source"] = COUNTER_SOURCE
+        l2_r["kernel_l2_GBps"] = L2_TO_CU_BYTES / (main_r["ms"] * 1e-3) / 1e9
+        l2_r["frac_of_hot_stream"] = l2_r["kernel_l2_GBps"] / l2_r["hot"]["GBps"]
     lib_r = measure_library_gemm(p, args.steps, args.warmup)
     lib_r["sparse_speedup_over_library_dense"] = lib_r["ms"] / main_r["ms"]
 
@@ -381,9 +429,8 @@ def main():
         for variant in range(9):
             q = synth.config(2, variant=variant)
             r = measure_spmm(q, args.steps, args.warmup, cold=True, graph=True)
-            d = measure_spmm(synth.config(2, variant=variant, sparsity=0.0), args.steps // 2 or 1,
-                             args.warmup, cold=True)
-            extra["config3_V%d_s%.2f" % (q.V, r["sparsity"])] = dict(r, dense_ms=d["ms"],
+            d = measure_spmm(synth.config(2, variant=variant, sparsity=0.0), args.steps, args.warmup, cold=True)
+            extra["config3_V%d_s%.2f" % (q.V, r["sparsity"])] = dict(r, dense_ms=d["ms"], dense_kernel=d["kernel"],
                                                                     speedup=d["ms"] / r["ms"])
         for variant in (3, 2, 1, 0):
             q = synth.config(4, variant=variant)
@@ -402,6 +449,11 @@ def main():
             json.dump(extra, f, indent=1)
         extra_file = "gpurun_out/bench_all.json"
     cpu = None if args.no_cpu else cpu_baseline(p)
+    # result check of what the timed launches left behind (oracle: part of the CPU leg)
+    checks = None
+    if not args.no_cpu:
+        checks = {"headline": check_sample(p, check_rows, main_sample),
+                  "dense_run": check_sample(dense_p, check_rows, dense_sample)}
 
     achieved = main_r["bytes"] / (main_r["ms"] * 1e-3)
     out = {
@@ -414,13 +466,17 @@ def main():
                    "M": p.M, "K": p.K, "N": p.N, "V": p.V, "nnz": main_r["nnz"],
                    "rotating_buffer_pairs": main_r["rotate"]},
         "roofline": {"bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK,
+                     "traffic": MEASURED_TRAFFIC_BYTES if counters_apply else None,
+                     "traffic_source": COUNTER_SOURCE if counters_apply else None,
                      "algorithmic_bytes_per_launch": main_r["bytes"],
-                     "kernel": "shflbw_slab_kernel<32,12,_Float16,false>"},
+                     "kernel": main_r["kernel"]},
         "mfma_peak_frac_useful": main_r["tflops"] * 1e12 / MFMA_F16_PEAK,
         "speedup_vs_own_dense": dense_r["ms"] / main_r["ms"],
-        "dense_run": {"ms": dense_r["ms"], "tflops": dense_r["tflops"],
+        "dense_run": {"ms": dense_r["ms"], "tflops": dense_r["tflops"], "kernel": dense_r["kernel"],
+                      "steps": args.steps, "warmup": args.warmup,
                       "mfma_peak_frac": dense_r["tflops"] * 1e12 / MFMA_F16_PEAK},
+        "result_check": checks,
         "warm_cache": {"ms": warm_r["ms"], "tflops": warm_r["tflops"]},
         "identity_perm": {"ms": ident_r["ms"], "shuffled_over_identity": main_r["ms"] / ident_r["ms"]},
         "conv2d_config4": conv_r,
@@ -434,6 +490,9 @@ def main():
     if extra_file:
         out["extra_file"] = extra_file
     print(json.dumps(out))
+    if checks and not all(c["ok"] for c in checks.values()):
+        print("bench.py: the timed launches left results outside the parity bound: %r" % checks, file=sys.stderr)
+        sys.exit(3)
 
 
 if __name__ == "__main__":

@@ -9,7 +9,8 @@
 //           (what the L2s can deliver into the CUs at best);
 //   mode 1  the slab kernel's grid and sharing pattern (workgroups that share
 //           a slab run side by side on one XCD), one pass, operands cold.
-// Built as its own small library (libshflbw_probe.so); only bench.py loads it.
+// Built as its own small library (bench_l2_probe.so, next to bench.py, by
+// bench.build_probe()); only bench.py loads it.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>

@@ -336,7 +336,7 @@ int shflbw_group_columns(const shflbw_matrix* A, int g, int32_t* cols, int cap)
     const int kg = A->kcount[g];
     if (!cols) return kg;
     if (cap < kg) return shflbw::fail(SHFLBW_ERR_BAD_SHAPE, "cols buffer too small");
-    const int32_t* src = &A->col_idx[(size_t)A->step_ptr[g] * A->TK];
+    const int32_t* src = A->col_idx.data() + (size_t)A->step_ptr[g] * A->TK;   // may be empty: no operator[]
     const size_t slots = (size_t)(A->step_ptr[g + 1] - A->step_ptr[g]) * A->TK;
     int n = 0;
     for (size_t t = 0; t < slots; ++t)

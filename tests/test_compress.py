@@ -193,6 +193,6 @@ def test_probe_library_loads_and_exports_its_entry_point():
     """The benchmark's L2 streaming probe is a library of its own (no compute call here)."""
     import ctypes
     import os
-    path = os.path.join(os.path.dirname(binding.__file__), "libshflbw_probe.so")
-    lib = ctypes.CDLL(path)
+    import bench
+    lib = ctypes.CDLL(bench.PROBE_LIB if os.path.exists(bench.PROBE_LIB) else bench.build_probe())
     assert hasattr(lib, "shflbw_probe_l2_stream")
