@@ -71,8 +71,8 @@ struct shflbw_matrix {
 namespace shflbw {
 #ifndef SHFLBW_SLAB_KC
 #define SHFLBW_SLAB_KC 64
-#define SHFLBW_SLAB_WINDOW 4
-#define SHFLBW_SLAB_LEAD 2
+#define SHFLBW_SLAB_WINDOW 3
+#define SHFLBW_SLAB_LEAD 3
 #endif
 constexpr int SLAB_KC = SHFLBW_SLAB_KC;          // rows of X per LDS chunk in the slab kernel
 constexpr int SLAB_WINDOW = SHFLBW_SLAB_WINDOW;  // adjacent chunks a k-step may span (readable at once)

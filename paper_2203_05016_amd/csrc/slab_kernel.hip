@@ -17,15 +17,17 @@
 // and the loaders never wait on weights.
 //
 // Residency and hand-over.  A ring of six 16 KB stages.  The packed matrix is
-// cut into k-steps whose columns span at most four adjacent chunks; a step
+// cut into k-steps whose columns span at most WINDOW = 3 adjacent chunks; a step
 // may run once the chunk c of its last column has landed, when chunks
-// c-3 .. c are resident.  There is no workgroup barrier in the loop.  Each
-// loader publishes in LDS how many chunks it has landed, each compute
-// wavefront the chunk of the step it is working on (it has finished every
-// step of an earlier chunk); a compute wavefront polls the former before a
-// step, a loader polls the latter only before it reuses a stage.  Wavefronts
-// therefore drift apart by up to two chunks, which is what overlaps one
-// wavefront's LDS latency with another's matrix-core time.  The polls are
+// c-2 .. c are resident; the other three stages are chunks in flight.  There
+// is no workgroup barrier in the loop.  Each loader publishes in LDS how many
+// chunks it has landed, each compute wavefront the chunk of the step it is
+// working on (it has finished every step of an earlier chunk); a compute
+// wavefront polls the former before a step, a loader looks at the latter
+// before it reuses a stage and never lets that hold back the announcement of
+// a chunk that has landed.  Wavefronts therefore drift apart by up to three
+// chunks, which is what overlaps one wavefront's LDS latency with another's
+// matrix-core time.  The polls are
 // bounded: a wavefront that does not see its condition within spin_limit
 // tries (about a million by default) goes on regardless - wrong numbers
 // instead of a hang - and sets a status word that the host can read back.
@@ -66,7 +68,7 @@ constexpr int SLAB_X_BYTES = (SLAB_ZERO_ROW + 1) * SLAB_ROW_BYTES;  // ring + th
 constexpr int SLAB_LOADERS = 4;                    // loader wavefronts per workgroup
 constexpr int SLAB_IPL = SLAB_KC / 4 / SLAB_LOADERS;  // direct loads (4 rows each) per loader per chunk
 static_assert(SLAB_IPL * SLAB_LOADERS * 4 == SLAB_KC, "chunk must divide evenly");
-static_assert(SLAB_IPL * (SLAB_LEAD - 1) < 16, "vmcnt immediates below use the low four bits only");
+static_assert(SLAB_IPL * (SLAB_LEAD - 1) < 64, "vmcnt is a six-bit count");
 
 constexpr int SLAB_BUFFER_FLAGS = 0x00020000;     // last word of a raw buffer descriptor: untyped 32-bit data
 
@@ -173,34 +175,42 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
                            x_off + (c % SLAB_STAGES) * SLAB_STAGE_BYTES + piece * 4 * SLAB_ROW_BYTES);
             }
         };
+        // `published` chunks have been announced to the compute wavefronts, `issued`
+        // requested.  A wavefront's loads complete in order, so "chunk `published` has
+        // landed" is a wait until only the loads of the younger chunks in flight remain.
+        // A landed chunk is announced at once, whether or not the ring has room for the
+        // next request: a fast compute wavefront may then run up to LEAD chunks ahead of
+        // the slowest one, whose progress is what frees a stage.  (Announcing chunk c+1
+        // only after the request for chunk c+LEAD had found its stage free kept every
+        // compute wavefront within one chunk of the slowest.)
+        int issued = 0, published = 0;
 #pragma unroll
         for (int c = 0; c < SLAB_LEAD; ++c)
-            if (c < C) issue_chunk(c);
-        for (int c = 0; c < C; ++c) {
-            // chunk c must have landed; chunks c+1 .. c+LEAD-1 (those that exist)
-            // are younger and may stay in flight
-            int younger = C - 1 - c;
-            younger = younger < SLAB_LEAD - 1 ? younger : SLAB_LEAD - 1;
-            switch (younger) {
+            if (c < C) { issue_chunk(c); issued = c + 1; }
+        while (published < C) {
+            switch (issued - published - 1) {   // chunks younger than the one awaited
                 case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
                 case 1: asm volatile("s_waitcnt vmcnt(%0)" :: "n"(SLAB_IPL) : "memory"); break;
                 case 2: asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * SLAB_IPL) : "memory"); break;
                 default: asm volatile("s_waitcnt vmcnt(%0)" :: "n"(3 * SLAB_IPL) : "memory"); break;
             }
             static_assert(SLAB_LEAD <= 4, "extend the switch above");
-            landed[lw] = c + 1;
-            const int j = c + SLAB_LEAD;
-            if (j < C) {
-                // chunk j takes the stage of chunk j-STAGES, whose last readers run
-                // in iteration j-LEAD-1 = c-1
-                if (j >= SLAB_STAGES) {
+            ++published;
+            landed[lw] = published;
+            // chunk j takes the stage of chunk j-STAGES, whose last readers are the steps that end
+            // in chunk j-LEAD-1: it may go out once every compute wavefront works on chunk j-LEAD or
+            // a later one
+            while (issued < C && issued - published < SLAB_LEAD) {
+                if (issued >= SLAB_STAGES && !reached(progress, GW, issued - SLAB_LEAD)) {
+                    if (issued > published) break;   // announce what is in flight first, then look again
                     int tries = 0;
-                    for (; !reached(progress, GW, c) && tries < a.spin_limit; ++tries)
+                    for (; !reached(progress, GW, issued - SLAB_LEAD) && tries < a.spin_limit; ++tries)
                         __builtin_amdgcn_s_sleep(1);
-                    if (tries >= a.spin_limit && !reached(progress, GW, c)) give_up(2);
+                    if (tries >= a.spin_limit && !reached(progress, GW, issued - SLAB_LEAD)) give_up(2);
                 }
                 asm volatile("" ::: "memory");
-                issue_chunk(j);
+                issue_chunk(issued);
+                ++issued;
             }
         }
         return;
