@@ -81,10 +81,29 @@ class Case:
                                  self.out_bytes)
 
 
+SETTLE_MS = 30.0   # untimed load before every timed leg, see time_steps
+
+
 def time_steps(fn, steps, warmup):
     """Average milliseconds per call of fn over `steps` calls, HIP events on
-    the stream the kernels are launched on (torch's current stream)."""
+    the stream the kernels are launched on (torch's current stream).
+
+    The GPU raises its clocks over the first ~10 ms of load: back-to-back batches of
+    100 launches of the headline product measured 44, 40 and 38 us per launch.  So
+    that a 20-step run and a 200-step run time the same machine state, every leg first
+    runs its own workload untimed for SETTLE_MS of GPU time, then the `warmup`
+    steps, then the timed steps."""
     import torch
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    spent = 0.0
+    while spent < SETTLE_MS:
+        e0.record()
+        for _ in range(50):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        spent += e0.elapsed_time(e1)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()

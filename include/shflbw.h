@@ -26,7 +26,9 @@
  *  - shflbw_spmm / shflbw_conv2d only enqueue work on the given HIP stream
  *    (a hipStream_t passed as void*; NULL = the default stream) and return
  *    without synchronising.  Launch errors are returned; execution errors
- *    surface at the caller's next synchronisation.
+ *    surface at the caller's next synchronisation.  One failure has no HIP
+ *    error: a bounded hand-over wait of the shared-slab kernel that ran out
+ *    (see shflbw_device_status); it shows as NaN in Y and in that status.
  *  - Y / out are fully overwritten (no accumulate-into).
  *  - Activations and weights are 16-bit floating point, IEEE binary16 or
  *    bfloat16 (one format per packed matrix, chosen at shflbw_compress);
@@ -156,8 +158,12 @@ int shflbw_set_tuning(shflbw_matrix* A, int kernel, int tile_n);
 /* The shared-slab kernel hands chunks of X from its loader wavefronts to its
  * compute wavefronts through flags in LDS (Alg. 1's pipeline, without
  * workgroup barriers).  Every wait on a flag is bounded: a wavefront that has
- * polled `tries` times goes on regardless, so a lost hand-over yields wrong
- * numbers, never a hang - and it sets a word in the matrix's device buffer.
+ * polled `tries` times goes on regardless, so a lost hand-over never hangs;
+ * it sets a word in the matrix's device buffer, and the failure is visible in
+ * the data: every 32 (V) x 128 output tile whose wavefront finished after a
+ * wait of its workgroup had run out is stored as NaN, so Y never holds
+ * plausible numbers computed from activations that were not there.  (This
+ * also holds for shflbw_conv2d where it runs as shflbw_spmm.)
  *
  * shflbw_device_status: waits for `stream`, reads that word back and clears
  *   it.  SHFLBW_OK if no wait ran out in any launch on this matrix since the

@@ -31,7 +31,7 @@ std::string kernel_name(const char* base, int V, int second, bool f32_out, bool 
 
 PackedView view_of(const shflbw_matrix* A)
 {
-    const char* b = static_cast<const char*>(A->dev_base);
+    const char* b = static_cast<const char*>(device_base(A));
     PackedView v;
     v.row_indices = reinterpret_cast<const int32_t*>(b + A->off_rows);
     v.step_ptr = reinterpret_cast<const int32_t*>(b + A->off_steps);
@@ -47,9 +47,10 @@ int launch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long l
 {
     SlabArgs a;
     a.A = view_of(A);
-    a.table = reinterpret_cast<const uint32_t*>(static_cast<const char*>(A->dev_base) + A->off_table);
-    a.first_chunk = reinterpret_cast<const int32_t*>(static_cast<const char*>(A->dev_base) + A->off_iter);
-    a.status = reinterpret_cast<int*>(static_cast<char*>(A->dev_base) + A->off_status);
+    char* base = static_cast<char*>(const_cast<void*>(device_base(A)));
+    a.table = reinterpret_cast<const uint32_t*>(base + A->off_table);
+    a.first_chunk = reinterpret_cast<const int32_t*>(base + A->off_iter);
+    a.status = reinterpret_cast<int*>(base + A->off_status);
     a.spin_limit = A->wait_limit;
     a.X = static_cast<const _Float16*>(X);
     a.Y = Y;
@@ -255,7 +256,7 @@ int dispatch_conv(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, shflbw_
 
 int check_bound(const shflbw_matrix* A)
 {
-    if (!A->dev_base) return fail(SHFLBW_ERR_NOT_ON_DEVICE, "call shflbw_bind_device first");
+    if (!device_base(A)) return fail(SHFLBW_ERR_NOT_ON_DEVICE, "call shflbw_bind_device first");
     return SHFLBW_OK;
 }
 

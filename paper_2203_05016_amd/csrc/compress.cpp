@@ -13,6 +13,7 @@
 namespace {
 thread_local std::string g_last_error;
 thread_local std::string g_last_kernel;
+thread_local const void* g_base_override = nullptr;
 
 // Position of (stored row i of the group, step column j) inside one k-step's
 // V*TK values; see the layout comment in shflbw_internal.h.
@@ -73,6 +74,8 @@ int fail(int status, const std::string& detail)
     return status;
 }
 void note_kernel(const std::string& name) { g_last_kernel = name; }
+const void* device_base(const shflbw_matrix* A) { return g_base_override ? g_base_override : A->dev_base; }
+void set_device_base_override(const void* base) { g_base_override = base; }
 }  // namespace shflbw
 
 extern "C" {

@@ -93,6 +93,10 @@ static_assert((SLAB_ZERO_ROW + 1) * SLAB_ROW_BYTES / 16 <= (1 << 13), "LDS offse
 constexpr int slab_swizzle(int r) { return ((r & 3) << 2) | (((r >> 2) & 1) << 1); }
 int fail(int status, const std::string& detail);  // records the thread-local text, returns status
 void note_kernel(const std::string& name);        // records what the calling thread launched last (shflbw_last_kernel)
+// Where the packed arrays of A live on the device for launches of the calling thread: the buffer given
+// to shflbw_bind_device, unless an entry point that brings its own device image has set an override.
+const void* device_base(const shflbw_matrix* A);
+void set_device_base_override(const void* base);  // nullptr = none; thread-local
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 }  // namespace shflbw
 

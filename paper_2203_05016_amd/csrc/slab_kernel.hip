@@ -110,7 +110,7 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     constexpr int SCRATCH_OFF = SLAB_X_BYTES;
     constexpr int FLAGS_OFF = SCRATCH_OFF + GW * WAVE_BYTES;  // landed[4], progress[GW]
     constexpr int LDS_BYTES = FLAGS_OFF + 128;
-    static_assert(SLAB_LOADERS + GW <= 32, "flag block");
+    static_assert(SLAB_LOADERS + GW <= 31, "flag block: landed, progress, and the last word for a wait that ran out");
     static_assert((SLAB_LOADERS & (SLAB_LOADERS - 1)) == 0, "the landed counts are read with lane & (SLAB_LOADERS - 1)");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
     __shared__ __attribute__((aligned(1024))) char smem[LDS_BYTES];
@@ -145,8 +145,15 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     };
     static_assert(GW <= 16 && SLAB_LOADERS + 16 + 16 <= 32 + 4, "flag reads stay inside the flag block");
     // a wait that ran out is recorded for the host (the wavefront goes on: wrong numbers, no hang)
+    // ... and for the workgroup: every compute wavefront that finishes after this stores NaN
+    // instead of a tile it cannot vouch for (a loader gives up only on behalf of a compute
+    // wavefront that still lags behind, a compute wavefront for itself)
+    lds_flag_ptr poisoned = landed + 31;
     auto give_up = [&](int who) __attribute__((always_inline)) {
-        if (lane == 0) atomicOr(a.status, who);
+        if (lane == 0) {
+            *poisoned = 1;
+            atomicOr(a.status, who);
+        }
     };
 
     if (wave >= GW) {
@@ -376,6 +383,7 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     const int erow = lane >> 3, echunk = lane & 7;        // 8 lanes x 16 B per row
     typedef OutT vec4 __attribute__((ext_vector_type(4)));
     typedef OutT vecw __attribute__((ext_vector_type(OUT16)));
+    const bool spoiled = *poisoned != 0;                  // a hand-over wait ran out: the tile is stored as NaN
 
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -401,6 +409,10 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
             for (int i = 0; i < ROWS_E / 8; ++i) {
                 const int row = i * 8 + erow;
                 vecw v = *reinterpret_cast<const vecw*>(ep + row * EP + echunk * OUT16);
+                if (spoiled) {
+#pragma unroll
+                    for (int j = 0; j < OUT16; ++j) v[j] = (OutT)__builtin_nanf("");
+                }
                 const int orig = out_row[rb][i];
                 const long n = n0 + pass * CW + echunk * OUT16;
                 if (n < a.N)

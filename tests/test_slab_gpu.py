@@ -147,10 +147,21 @@ def test_slab_reports_a_wait_that_ran_out():
     A.device_status()                      # nothing ran out
     assert_within_scaled_tolerance(Y.cpu().numpy(), Yr, S, what="before")
     A.set_wait_limit(0)
-    A.spmm(X)
+    Ybad = A.spmm(X)
     with pytest.raises(binding.ShflbwError) as e:
         A.device_status()
     assert e.value.status == -10
+    # the failure is visible in the data: a tile whose wavefront gave up (or finished after a
+    # wait of its workgroup ran out) is NaN, every other element is right - never a
+    # plausible wrong number
+    Yb = Ybad.cpu().numpy().astype(np.float64)
+    bad = np.isnan(Yb)
+    assert bad.any(), "no tile was poisoned although every wait gave up at once"
+    assert np.all(np.abs(Yb[~bad] - Yr[~bad]) <= 2.0 ** -10 * S[~bad])
+    # poisoning goes by whole 32-row x 128-column tiles
+    rows_of_group0 = p.perm[:32]
+    block = bad[np.ix_(rows_of_group0, np.arange(128))]
+    assert block.all() or not block.any()
     A.device_status()                      # the word was cleared
     A.set_wait_limit(1 << 20)
     Y = A.spmm(X)
