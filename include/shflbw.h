@@ -190,6 +190,28 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
                 int64_t N, shflbw_dtype ydtype, void* stream);
 
 /*
+ * shflbw_spmm for callers that cannot allocate device memory (code that runs where
+ * hipMalloc is forbidden or fails: tight serving loops, harnesses that own all device
+ * memory): the packed arrays go into a device image that the library itself holds, a
+ * static array of SHFLBW_UNBOUND_MAX_BYTES on every GPU it is used on, instead of a
+ * caller-owned buffer; no shflbw_bind_device is needed, and a binding the handle may have
+ * is neither used nor changed.  Every call copies A's packed arrays (host to device, on
+ * `stream`), clears the hand-over status block with a small kernel, and launches exactly
+ * what shflbw_spmm launches; X, Y and the result are those of shflbw_spmm, bit for bit.
+ * Allocates nothing (no hipMalloc / hipFree).
+ *  - A packed matrix larger than SHFLBW_UNBOUND_MAX_BYTES (see shflbw_device_bytes) is
+ *    refused with SHFLBW_ERR_BAD_SHAPE.
+ *  - All calls on one GPU share the one image, which keeps the last call's contents: calls
+ *    whose work can overlap on a GPU (different streams, different threads) race on it and
+ *    must be ordered by the caller.  Calls on one stream are ordered by the stream.
+ *  - The host arrays of A are read until the copies have been issued; with pageable host
+ *    memory the runtime has consumed them when the call returns.
+ */
+#define SHFLBW_UNBOUND_MAX_BYTES (8u << 20)
+int shflbw_spmm_unbound(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int64_t ldy,
+                        int64_t N, shflbw_dtype ydtype, void* stream);
+
+/*
  * 2-D convolution as implicit GEMM (Section 4.1): the unfolded feature map
  * exists only in on-chip buffers.  A has M = C_out rows and K = C_in*R*S
  * columns flattened as k = (c*R + r)*S + s.  Cross-correlation (no kernel

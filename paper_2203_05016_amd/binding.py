@@ -22,7 +22,8 @@ _lib = None
 EXPORTS = [
     "shflbw_compress", "shflbw_pattern_search", "shflbw_destroy", "shflbw_info", "shflbw_row_indices",
     "shflbw_group_columns", "shflbw_decompress", "shflbw_device_bytes", "shflbw_bind_device",
-    "shflbw_set_tuning", "shflbw_device_status", "shflbw_set_wait_limit", "shflbw_spmm", "shflbw_conv2d",
+    "shflbw_set_tuning", "shflbw_device_status", "shflbw_set_wait_limit", "shflbw_spmm", "shflbw_spmm_unbound",
+    "shflbw_conv2d",
     "shflbw_layernorm_transpose", "shflbw_status_string", "shflbw_last_error", "shflbw_last_kernel",
 ]
 
@@ -66,6 +67,8 @@ def lib():
         L.shflbw_set_wait_limit.argtypes = [vp, i32]
         L.shflbw_spmm.restype = i32
         L.shflbw_spmm.argtypes = [vp, vp, i64, vp, i64, i64, i32, vp]
+        L.shflbw_spmm_unbound.restype = i32
+        L.shflbw_spmm_unbound.argtypes = [vp, vp, i64, vp, i64, i64, i32, vp]
         L.shflbw_conv2d.restype = i32
         L.shflbw_conv2d.argtypes = [vp, vp, vp] + [i32] * 10 + [i32, i32, vp]
         L.shflbw_pattern_search.restype = i32

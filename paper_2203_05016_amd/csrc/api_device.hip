@@ -4,6 +4,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 
 #include "gather_kernel.hip"
@@ -14,6 +15,19 @@
 
 namespace shflbw {
 namespace {
+
+// Device image of one packed matrix for shflbw_spmm_unbound: the library's own memory,
+// one copy per GPU, held until the process ends.
+constexpr size_t STATIC_IMAGE_BYTES = SHFLBW_UNBOUND_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_IMAGE_BYTES];
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES];          // address of `scratch` on each device, resolved on first use
+std::mutex g_scratch_mutex;
+
+__global__ void clear_status_kernel(int* word)
+{
+    if (threadIdx.x < 64) word[threadIdx.x] = 0;
+}
 
 int hip_fail(hipError_t e, const char* what)
 {
@@ -381,6 +395,57 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
     }
     GeomLinear<false> g{static_cast<const _Float16*>(X), Y, (long)ldx, (long)ldy, (long)N};
     return dispatch_out(A, g, (long)N, ydtype, st);
+}
+
+int shflbw_spmm_unbound(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int64_t ldy,
+                        int64_t N, shflbw_dtype ydtype, void* stream)
+{
+    using namespace shflbw;
+    if (!A) return fail(SHFLBW_ERR_NULL_ARG, "A is NULL");
+    if (A->dev_bytes > STATIC_IMAGE_BYTES)
+        return fail(SHFLBW_ERR_BAD_SHAPE, "packed matrix of " + std::to_string(A->dev_bytes) +
+                    " bytes exceeds the library's static device image of " + std::to_string(STATIC_IMAGE_BYTES) +
+                    " bytes (SHFLBW_UNBOUND_MAX_BYTES): bind it to a buffer of your own and call shflbw_spmm");
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(SHFLBW_ERR_HIP, "device ordinal out of range");
+    char* base;
+    {
+        // the array's name is a host-side stand-in: its device address comes from the runtime, per device
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+            g_scratch_ptr[dev] = p;
+        }
+        base = static_cast<char*>(g_scratch_ptr[dev]);
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    struct Part { size_t off; const void* src; size_t bytes; };
+    const Part parts[] = {
+        {A->off_rows, A->row_indices.data(), A->row_indices.size() * sizeof(int32_t)},
+        {A->off_steps, A->step_ptr.data(), A->step_ptr.size() * sizeof(int32_t)},
+        {A->off_iter, A->first_chunk.data(), A->first_chunk.size() * sizeof(int32_t)},
+        {A->off_cols, A->col_idx.data(), A->col_idx.size() * sizeof(int32_t)},
+        {A->off_table, A->slab_table.data(), A->slab_table.size() * sizeof(uint32_t)},
+        {A->off_vals, A->values.data(), A->values.size() * sizeof(uint16_t)},
+    };
+    for (const Part& p : parts) {
+        if (!p.bytes) continue;
+        e = hipMemcpyAsync(base + p.off, p.src, p.bytes, hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync");
+    }
+    // the status block keeps the last call's contents: it must start at zero (a kernel, not a
+    // memset node, so that the call can also be recorded into a graph)
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, st, reinterpret_cast<int*>(base + A->off_status));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    set_device_base_override(base);
+    const int rc = shflbw_spmm(A, X, ldx, Y, ldy, N, ydtype, stream);
+    set_device_base_override(nullptr);
+    return rc;
 }
 
 int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, int C_in, int H,
