@@ -72,8 +72,18 @@ int launch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long l
     a.K = A->K; a.C = A->slab_chunks;
     const long n_tiles = (N + SLAB_TN - 1) / SLAB_TN;
     a.n_tiles = (int)n_tiles;
-    a.gblocks = (A->G + GW - 1) / GW;
-    const long wgs = ((n_tiles + 7) / 8) * 8 * a.gblocks;
+    constexpr int GROUPS = V == 128 ? GW / 2 : GW;   // row groups per workgroup
+    a.gblocks = (A->G + GROUPS - 1) / GROUPS;
+    long wgs = ((n_tiles + 7) / 8) * 8 * a.gblocks;
+    // packed weights well beyond an L2: blocks of 8 group blocks x 4 column tiles per XCD
+    // (fabric traffic of 8192 x 8192 x 16384 at 75 %: 2.7 -> 1.6 GB); the column tiles of an
+    // XCD are rounded up to whole blocks
+    a.gb_side = 0;
+    if (a.gblocks % 8 == 0 && A->values.size() * sizeof(uint16_t) > (size_t)(16 << 20)) {
+        a.gb_side = 8;
+        const long per_xcd = (n_tiles + 7) / 8;                 // column tiles of one XCD
+        wgs = (per_xcd + 3) / 4 * 4 * 8 * a.gblocks;
+    }
     if (wgs > 0x7fffffffL) return fail(SHFLBW_ERR_BAD_SHAPE, "grid too large");
     hipLaunchKernelGGL((shflbw_slab_kernel<V, GW, OutT, BF>), dim3((unsigned)wgs), dim3(64 * (GW + SLAB_LOADERS)), 0,
                        stream, a);
@@ -91,8 +101,9 @@ int dispatch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long
         case 16: return launch_slab<16, 12, OutT, BF>(A, X, ldx, Y, ldy, N, stream);
         case 32: return launch_slab<32, 12, OutT, BF>(A, X, ldx, Y, ldy, N, stream);
         case 64: return launch_slab<64, 8, OutT, BF>(A, X, ldx, Y, ldy, N, stream);
+        case 128: return launch_slab<128, 8, OutT, BF>(A, X, ldx, Y, ldy, N, stream);
     }
-    return fail(SHFLBW_ERR_BAD_OPTION, "the slab kernel supports V = 16, 32, 64");
+    return fail(SHFLBW_ERR_BAD_OPTION, "the slab kernel supports V = 16, 32, 64, 128");
 }
 
 // The gather kernel's instantiations live in their own translation units, one per
@@ -350,21 +361,26 @@ int shflbw_spmm(const shflbw_matrix* A, const void* X, int64_t ldx, void* Y, int
     const bool aligned = (N % 8 == 0) && (ldx % 8 == 0) && (ldy % 8 == 0) &&
                          (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
-    const bool slab_possible = aligned && A->slab_ok && A->V <= 64;
+    const bool slab_possible = aligned && A->slab_ok;
     if (A->tune_kernel == 2 && !slab_possible)
-        return fail(SHFLBW_ERR_BAD_OPTION, "slab kernel needs the windowed layout, V <= 64 and aligned operands");
+        return fail(SHFLBW_ERR_BAD_OPTION, "slab kernel needs the windowed layout and aligned operands");
     bool use_slab = A->tune_kernel == 2;
     if (A->tune_kernel == 0 && slab_possible) {
         // automatic choice, from timings of both kernels over the benchmark shapes: the
         // slab kernel streams all of X whatever the sparsity, so it pays when enough of
         // each chunk is used (density), sooner on problems with many tiles; it also
         // needs enough groups to fill its compute wavefronts
-        const int gw = A->V == 64 ? 8 : 12;
+        const int gw = A->V == 128 ? 4 : A->V == 64 ? 8 : 12;   // groups per workgroup
         const long tiles = ((N + SLAB_TN - 1) / SLAB_TN) * ((A->G + gw - 1) / gw);
         const double density = (double)A->nnz / ((double)A->M * A->K);
-        // (crossovers measured at 85 % sparsity for V = 16 and 32, 78-80 % for V = 64, whose
-        // gathered bytes serve twice the rows)
-        const double need = tiles >= 128 ? (A->V == 64 ? 0.22 : 0.17) : 0.6;
+        // Crossovers measured with at least one workgroup per CU: 85 % sparsity for V = 16 and
+        // 32, 80-83 % for V = 64 and 128, whose gathered bytes serve more rows.  With fewer
+        // workgroups the slab kernel leaves part of the chip idle: from half a round it still pays
+        // on the denser half of the range, below that only for V = 16 (whose gather kernel has
+        // the least reuse), and on nearly dense matrices.
+        double need;
+        if (A->V == 16) need = tiles >= 128 ? 0.17 : 0.6;
+        else need = tiles >= 256 ? (A->V >= 64 ? 0.19 : 0.17) : tiles >= 128 ? 0.5 : 2.0;
         // very few column tiles: the gather kernel with split k-steps fills the chip better
         const bool skinny = ((N + 63) / 64) * A->G <= 512;
         use_slab = A->G >= gw && density >= need && !skinny;

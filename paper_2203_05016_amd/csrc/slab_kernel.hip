@@ -1,7 +1,7 @@
 // Shared-slab kernel for the Shfl-BW product on gfx950 (CDNA4).
 //
-// A workgroup owns GW row groups (one compute wavefront each) x 128 output
-// columns.  All of its wavefronts need rows of the same 128-column slab of X,
+// A workgroup owns GW row groups (one compute wavefront each; for V = 128 two
+// wavefronts share a group, 64 of its rows each) x 128 output columns.  All of its wavefronts need rows of the same 128-column slab of X,
 // each a different subset, so the slab is streamed through LDS once, DENSE,
 // in chunks of KC = 64 rows, and the stitching of Section 4.3 happens at
 // LDS-read time: the transposing LDS read takes one address per lane, so a
@@ -93,6 +93,7 @@ struct SlabArgs {
     long ldx, ldy, N;
     int K, C;
     int n_tiles, gblocks;     // 128-column tiles, blocks of GW groups
+    int gb_side;              // 0, or the group-block side of the blocks an XCD works on at a time (divides gblocks, and 32)
     int spin_limit;           // polls per bounded wait
     int* status;              // set to non-zero by a wavefront whose wait ran out
 };
@@ -102,7 +103,11 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
 {
     constexpr bool SMALL = (V == 16);
     constexpr int TK = SMALL ? 32 : 16;
-    constexpr int RB = SMALL ? 1 : V / 32;
+    constexpr int RBG = SMALL ? 1 : V / 32;           // 32-row blocks of a group
+    constexpr int SPLITW = V == 128 ? 2 : 1;          // compute wavefronts per group: V = 128 is shared by two,
+                                                      // same steps and X rows, two row blocks of the weights each
+    constexpr int RB = RBG / SPLITW;                  // row blocks (accumulator sets) of one wavefront
+    static_assert(GW % SPLITW == 0, "whole groups per workgroup");
     constexpr int TILE_N = SMALL ? 16 : 32;
     constexpr int NT = SLAB_TN / TILE_N;
     constexpr int PD = RB >= 2 ? 2 : SLAB_UNROLL;     // register sets of prefetched metadata (divides SLAB_UNROLL)
@@ -122,10 +127,24 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     // Workgroups are dealt round-robin to the 8 XCDs; the blocks that share a
     // slab of X (same column tile, different group blocks) are given ids that
     // land on the same XCD one after the other, so its L2 serves the re-reads.
+    //
+    // When the packed weights are far larger than an L2 (4 MB per XCD), running all group
+    // blocks of two column tiles side by side makes every workgroup fetch its weights over the
+    // fabric.  The 32 workgroups an XCD runs at a time then form a block of gb_side group blocks
+    // x 32/gb_side column tiles instead: weights are fetched once per 32/gb_side column tiles,
+    // activations once per gb_side group blocks.
     const int wg = blockIdx.x;
     const int xcd = wg & 7, wslot = wg >> 3;
-    const int gb = wslot % a.gblocks;
-    const int nt = (wslot / a.gblocks) * 8 + xcd;
+    int gb, nt;
+    if (a.gb_side == 0) {
+        gb = wslot % a.gblocks;
+        nt = (wslot / a.gblocks) * 8 + xcd;
+    } else {
+        const int side_n = 32 / a.gb_side, blocks_g = a.gblocks / a.gb_side;
+        const int block = wslot >> 5, inside = wslot & 31;
+        gb = (block % blocks_g) * a.gb_side + inside % a.gb_side;
+        nt = ((block / blocks_g) * side_n + inside / a.gb_side) * 8 + xcd;
+    }
     if (nt >= a.n_tiles) return;  // uniform for the whole workgroup
     const long n0 = (long)nt * SLAB_TN;
     const int C = a.C;
@@ -224,7 +243,8 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     }
 
     // ---------------------------------------------------------------- compute
-    const int g = gb * GW + wave;
+    const int g = gb * (GW / SPLITW) + wave / SPLITW;
+    const int half = wave % SPLITW;                   // which of the group's row-block halves (V = 128)
     const bool have_group = g < a.A.G;
     if (!have_group) {
         progress[wave] = C;  // nothing to read: never hold a stage back
@@ -253,7 +273,7 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     int out_row[RB][ROWS_E / 8];
     constexpr bool EARLY_ROWS = RB < 2;   // with two row blocks the registers are needed in the loop
     auto load_rows = [&]() __attribute__((always_inline)) {
-        const int32_t* rows_g = a.A.row_indices + (long)g * V;
+        const int32_t* rows_g = a.A.row_indices + (long)g * V + half * RB * 32;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -279,13 +299,13 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     const int qc = SMALL ? ((il & 3) >> 1) : (2 * (bl & 1) + ((il & 3) >> 1));
     const unsigned lane_bits = (unsigned)(qc << 4) | (unsigned)((il & 1) << 3);
     const __amdgpu_buffer_rsrc_t val_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<half8*>(a.A.values + (long)sbeg * RB * 64), 0, nsteps * RB * 1024, SLAB_BUFFER_FLAGS);
+        const_cast<half8*>(a.A.values + (long)sbeg * RBG * 64), 0, nsteps * RBG * 1024, SLAB_BUFFER_FLAGS);
     auto load_table = [&](int s) __attribute__((always_inline)) {
         return __builtin_amdgcn_raw_buffer_load_b32(tab_rsrc, pair * 4, s * (WPS * 4), 0);
     };
     auto load_weights = [&](int s, int rb) __attribute__((always_inline)) {
         return __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, lane * 16,
-                                                                                (s * RB + rb) * 1024, 0));
+                                                                                (s * RBG + half * RB + rb) * 1024, 0));
     };
     unsigned mt[PD];
     half8 mw[PD][RB];

@@ -24,7 +24,7 @@ def test_slab_config1_tiny(out_dtype):
     _parity(synth.config(0), out_dtype=out_dtype)
 
 
-@pytest.mark.parametrize("V", [16, 32, 64])
+@pytest.mark.parametrize("V", [16, 32, 64, 128])
 def test_slab_integer_inputs_bit_exact(V):
     announce("slab integer", V)
     p = synth.make_spmm(20 * V, 400, 264, V, 0.6, seed=131 + V, integer=True)
@@ -36,7 +36,8 @@ def test_slab_integer_inputs_bit_exact(V):
 
 
 @pytest.mark.parametrize("V,K,sp", [(16, 333, 0.5), (32, 333, 0.5), (32, 1000, 0.75),
-                                    (64, 520, 0.6), (32, 128, 0.0), (64, 384, 0.0)])
+                                    (64, 520, 0.6), (32, 128, 0.0), (64, 384, 0.0),
+                                    (128, 520, 0.6), (128, 333, 0.0)])
 def test_slab_multi_tile_ragged(V, K, sp):
     """Several column tiles with a ragged tail (N = 8*59), K not a multiple of
     the chunk, group counts that leave wavefronts of the last block idle."""
@@ -56,6 +57,28 @@ def test_slab_variable_kept_counts_and_empty_groups():
     assert np.all(Y[rows] == 0)
     Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
     assert_within_scaled_tolerance(Y, Yr, S, what="slab ragged groups")
+
+
+def test_slab_v128_two_wavefronts_per_group():
+    """V = 128: two compute wavefronts share a group (64 of its rows each, the same
+    steps and activation rows).  An odd number of groups leaves half a workgroup idle,
+    ragged kept counts and an empty group; both output types; the gather kernel on
+    exact inputs must give the same bits."""
+    announce("slab V=128")
+    p = synth.make_spmm(5 * 128, 700, 392, 128, 0.5, seed=171, ragged=True)
+    rows = p.perm[128:256]
+    p.mask[rows] = 0
+    p.cols[1] = np.zeros((0,), dtype=np.int64)
+    Yr, S = c_oracle.spmm(p.W, p.mask, p.X)
+    for out_dtype in ("float16", "float32"):
+        Y = run_spmm(p, kernel=SLAB, out_dtype=out_dtype)
+        assert np.all(Y[rows] == 0)
+        assert_within_scaled_tolerance(Y, Yr, S, what="slab V=128 " + out_dtype)
+    q = synth.make_spmm(3 * 128, 640, 264, 128, 0.75, seed=172, integer=True)
+    assert np.array_equal(run_spmm(q, kernel=1).view(np.uint16), run_spmm(q, kernel=SLAB).view(np.uint16))
+    b = synth.make_spmm(2 * 128, 384, 136, 128, 0.5, seed=173, fmt="bf16")
+    Yb, Sb = c_oracle.spmm(b.W, b.mask, b.X)
+    assert_within_scaled_tolerance(run_spmm(b, kernel=SLAB, out_dtype="float32"), Yb, Sb, what="slab V=128 bf16")
 
 
 def test_slab_matches_gather_kernel_on_exact_inputs():
