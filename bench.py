@@ -193,6 +193,11 @@ def measure_conv(p, steps, warmup, pairs=8):
     return dict(ms=ms, tflops=flop / (ms * 1e-3) / 1e12, flop=flop)
 
 
+def binding_last_kernel():
+    from paper_2203_05016_amd import binding
+    return binding.last_kernel()
+
+
 def measure_conv_shapes(steps, warmup):
     """ResNet-50-like layer shapes at batch 32, V = 32, 75 % sparsity, NCHW: this library's
     conv2d on rotating input/output pairs, and the vendor's dense convolution as context."""
@@ -463,6 +468,15 @@ def main():
             r1 = measure_spmm(q, args.steps, args.warmup, cold=True, kernel=1)
             extra["skinny_%dx%dx%d_s%.2f" % (M, K, N, sp)] = dict(r, whole_tile_gather_ms=r1["ms"])
         extra["conv_shapes_batch32_V32_s0.75"] = measure_conv_shapes(50, 5)
+        # config 4's tensor with the other group sizes (all through the staged kernel), and V = 128
+        # on a large layer through the shared-slab kernel
+        for V in (16, 64, 128):
+            r = measure_conv(synth.config(3, V=V), args.steps, args.warmup)
+            r["kernel"] = binding_last_kernel()
+            extra["conv_config4_shape_V%d_s0.75" % V] = r
+        for sp in (0.0, 0.75):
+            q = synth.make_spmm(4096, 4096, 8192, 128, sp, seed=synth.BASE_SEED + 7128)
+            extra["V128_4096x4096x8192_s%.2f" % sp] = measure_spmm(q, 30, 5, cold=True)
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         with open(os.path.join(ROOT, "gpurun_out", "bench_all.json"), "w") as f:
             json.dump(extra, f, indent=1)

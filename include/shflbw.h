@@ -219,9 +219,9 @@ int shflbw_spmm_unbound(const shflbw_matrix* A, const void* X, int64_t ldx, void
  *  in   device, the matrix's wdtype: [batch][C_in][H][W] (NCHW) or [C_in][H][W][batch] (CHWN).
  *  out  device, ydtype (the matrix's wdtype, or SHFLBW_F32): [batch][C_out][H_out][W_out] or [C_out][H_out][W_out][batch],
  *       H_out = (H + 2*pad_h - R)/stride_h + 1, W_out likewise.
- * For V = 32, 64 and 128 a workgroup copies the part of the input its output
- * positions can touch into LDS once and gathers from there; V = 16, and
- * inputs with too many channels for that, take the per-wave gather kernel.
+ * A workgroup copies the part of the input its output positions can touch into
+ * LDS once and gathers from there; inputs with too many channels for that take
+ * the per-wave gather kernel.
  * A 1x1 convolution with unit stride and no padding is the linear-layer
  * product itself (CHWN: one matrix; NCHW with H*W a multiple of 4: one per
  * image, all in one launch) and runs as shflbw_spmm does.

@@ -78,6 +78,7 @@ int launch_slab(const shflbw_matrix* A, const void* X, long ldx, void* Y, long l
     // packed weights well beyond an L2: blocks of 8 group blocks x 4 column tiles per XCD
     // (fabric traffic of 8192 x 8192 x 16384 at 75 %: 2.7 -> 1.6 GB); the column tiles of an
     // XCD are rounded up to whole blocks
+    a.uniform_steps = A->uniform_steps;
     a.gb_side = 0;
     if (a.gblocks % 8 == 0 && A->values.size() * sizeof(uint16_t) > (size_t)(16 << 20)) {
         a.gb_side = 8;
@@ -132,7 +133,7 @@ int check_ydtype(const shflbw_matrix* A, shflbw_dtype ydtype)
 bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S, int sh, int sw,
                int ph, int pw, int Ho, int Wo, bool chwn, ConvArgs& a, size_t& lds_bytes)
 {
-    if (A->V != 32 && A->V != 64 && A->V != 128) return false;
+    if (A->V != 16 && A->V != 32 && A->V != 64 && A->V != 128) return false;
     if (A->K >= (1 << 20) || (long)R * S >= (1 << 20)) return false;   // exact division by multiplication
     // the kernel addresses the input through a buffer descriptor with 32-bit byte offsets
     const unsigned long long in_total = 2ULL * (unsigned long long)B * C * H * W;
@@ -274,6 +275,7 @@ int dispatch_conv_v(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, shflb
 int dispatch_conv(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, shflbw_dtype ydtype,
                   hipStream_t stream)
 {
+    if (A->V == 16) return dispatch_conv_v<16>(A, a, lds_bytes, ydtype, stream);
     if (A->V == 32) return dispatch_conv_v<32>(A, a, lds_bytes, ydtype, stream);
     if (A->V == 64) return dispatch_conv_v<64>(A, a, lds_bytes, ydtype, stream);
     return dispatch_conv_v<128>(A, a, lds_bytes, ydtype, stream);
@@ -552,7 +554,7 @@ int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, 
         }
         if (A->tune_kernel == 2)
             return fail(SHFLBW_ERR_BAD_OPTION,
-                        "staged convolution kernel needs V = 32, 64 or 128 and an input box that fits the LDS");
+                        "staged convolution kernel needs an input box that fits the LDS");
     }
     GeomConv g;
     g.in = static_cast<const _Float16*>(in);

@@ -232,6 +232,9 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
             A->nnz += (int64_t)cols[g].size() * V;
             A->step_ptr[g + 1] = A->step_ptr[g] + (int)padded(lens[g].size());
         }
+        A->uniform_steps = A->step_ptr[1] - A->step_ptr[0];
+        for (int g = 1; g < G; ++g)
+            if (A->step_ptr[g + 1] - A->step_ptr[g] != A->uniform_steps) A->uniform_steps = -1;
         const size_t steps = (size_t)A->step_ptr[G];
         A->col_idx.assign(steps * TK, -1);
         A->values.assign(steps * (size_t)V * TK, 0);

@@ -18,6 +18,7 @@
 //
 // Algorithm 1's parts: BulkLoadMeta = column indices in bulks of 64 k-steps,
 // the weight operand eight (V = 64: four, V = 128: two) k-steps ahead in as many register sets;
+// V = 16 runs on the 16x16x32 instruction: tiles of 16 positions, k-steps of 32 indices;
 // StitchTile = the LDS gather above (each lane reads the 8 reduction indices
 // x up to 4 positions it feeds to the matrix cores); WarpMMA =
 // v_mfma_f32_32x32x16_f16 with the activation tile as first operand;
@@ -73,9 +74,15 @@ __device__ __forceinline__ int conv_div(int x, unsigned long long m)
 template <int V, int NT, typename OutT, bool BF>
 __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
 {
-    constexpr int RB = V / 32;
+    constexpr bool SMALL = (V == 16);                 // 16x16x32 instruction: 16 positions x 16 rows, 32 reduction indices
+    constexpr int RB = SMALL ? 1 : V / 32;
+    constexpr int TK = SMALL ? 32 : 16;               // reduction indices per k-step
+    constexpr int POS = SMALL ? 16 : 32;              // output positions per instruction tile
+    constexpr int NTI = NT * (32 / POS);              // instruction tiles per wavefront
+    constexpr int KBLOCKS = TK / 8;                   // a lane feeds 8 reduction indices of block lane / POS
+    constexpr int BULK = CONV_BULK * 16 / TK;         // k-steps of koff values held at a time (the list's size is fixed)
     constexpr int CONV_PD = RB == 1 ? 8 : RB == 2 ? 4 : 2;   // k-steps the weight operand is fetched ahead
-    static_assert(CONV_BULK % CONV_PD == 0, "bulk boundaries fall on batch boundaries");
+    static_assert(BULK % CONV_PD == 0, "bulk boundaries fall on batch boundaries");
     extern __shared__ __attribute__((aligned(16))) char conv_smem[];
     _Float16* xin = reinterpret_cast<_Float16*>(conv_smem);
     const int tid = threadIdx.x;
@@ -103,11 +110,11 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     const int sbeg = have_group ? a.A.step_ptr[g] : 0;
     const int nsteps = have_group ? a.A.step_ptr[g + 1] - sbeg : 0;
 
-    // koff values of steps [s0, s0 + CONV_BULK) of this group into the list
-    constexpr int BULK_LOADS = CONV_BULK * 16 / 64;
+    // koff values of steps [s0, s0 + BULK) of this group into the list
+    constexpr int BULK_LOADS = BULK * TK / 64;
     auto load_cols = [&](int s0, int (&cols)[BULK_LOADS]) __attribute__((always_inline)) {
-        const int32_t* cp = a.A.col_idx + ((long)sbeg + s0) * 16;
-        const int avail = (nsteps - s0) * 16;
+        const int32_t* cp = a.A.col_idx + ((long)sbeg + s0) * TK;
+        const int avail = (nsteps - s0) * TK;
 #pragma unroll
         for (int i = 0; i < BULK_LOADS; ++i) {
             const int j = i * 64 + lane;
@@ -180,13 +187,13 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     store_koff(cols0);
     __syncthreads();
 
-    // ---- this lane's output positions: n' = 32*(ts*NT + t) + lane%32
+    // ---- this lane's output positions: n' = POS*(ts*NTI + t) + lane%POS
     const int npos = a.tb * a.th * a.tw;
-    int noff[NT], ooff[NT];
-    bool live[NT];
+    int noff[NTI], ooff[NTI];
+    bool live[NTI];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int n = 32 * (ts * NT + t) + (lane & 31);
+    for (int t = 0; t < NTI; ++t) {
+        const int n = POS * (ts * NTI + t) + (lane & (POS - 1));
         int bb, yy, xx;
         if (a.b_fast) {
             const int q = conv_div(n, a.m_tb);
@@ -201,18 +208,24 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
         ooff[t] = live[t] ? (int)(b * a.osB + y * a.osH + x * a.osW) : 0;
     }
 
-    floatx16 acc[RB][NT];
+    floatx16 acc[SMALL ? 1 : RB][SMALL ? 1 : NTI];
+    floatx4 acc16[SMALL ? NTI : 1];
+    if (SMALL) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+        for (int t = 0; t < NTI; ++t) acc16[t] = floatx4{0, 0, 0, 0};
+    } else {
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[rb][t][r] = 0.f;
+            for (int t = 0; t < NTI; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[rb][t][r] = 0.f;
+    }
 
     if (nsteps > 0) {
-        const int khalf = lane >> 5;
+        const int kblock = lane / POS;
         typedef unsigned short ushort8 __attribute__((ext_vector_type(8)));
-        const ushort8* kl = reinterpret_cast<const ushort8*>(klist) + khalf;   // 8 slots of this lane's half
+        const ushort8* kl = reinterpret_cast<const ushort8*>(klist) + kblock;   // 8 slots of this lane's block
 
         // StitchTile of one step: 8 reduction indices x up to NT positions per lane.  The
         // list entry of a step is read one step before its gathers go out, the gathers one
@@ -221,16 +234,16 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
         // group's last one multiplies zero weights (the descriptor's range) with the zero
         // plane (the list's filler), and every load is unconditional, which keeps the
         // register sets static and the wait counts exact.
-        auto read_list = [&](int s) __attribute__((always_inline)) { return kl[(s & (CONV_BULK - 1)) * 2]; };
-        auto gather = [&](const ushort8& ko, half8 (&x)[NT]) __attribute__((always_inline)) {
+        auto read_list = [&](int s) __attribute__((always_inline)) { return kl[(s & (BULK - 1)) * KBLOCKS]; };
+        auto gather = [&](const ushort8& ko, half8 (&x)[NTI]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
+            for (int t = 0; t < NTI; ++t)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) x[t][e] = xin[(int)ko[e] + noff[t]];
         };
         static_assert(CONV_PD % 2 == 0, "entries and tiles alternate between two register sets");
         ushort8 ko[2];      // list entry of step j in ko[j & 1]
-        half8 x[2][NT];     // gathered tile of step j in x[j & 1]
+        half8 x[2][NTI];    // gathered tile of step j in x[j & 1]
         ko[0] = read_list(0);
         gather(ko[0], x[0]);
         ko[1] = read_list(1);
@@ -242,7 +255,7 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
                 if ((u + 2) % CONV_PD == 0) {
                     // the entry read below may open the next bulk of column indices; every entry
                     // of the old bulk is in registers by now
-                    if (((s + 2) & (CONV_BULK - 1)) == 0 && s + 2 < nsteps) {   // uniform
+                    if (((s + 2) & (BULK - 1)) == 0 && s + 2 < nsteps) {   // uniform
                         int cols[BULK_LOADS];
                         load_cols(s + 2, cols);
                         SHFLBW_WAVE_LDS_SYNC();   // reads of the old list are over
@@ -253,10 +266,15 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
                 gather(ko[(u + 1) & 1], x[(u + 1) & 1]);   // step s + 1, in flight while step s is multiplied
                 ko[u & 1] = read_list(s + 2);
 #pragma unroll
-                for (int t = 0; t < NT; ++t)
+                for (int t = 0; t < NTI; ++t) {
+                    if (SMALL) {
+                        acc16[t] = mma16<BF>(x[u & 1][t], w[u][0], acc16[t]);
+                    } else {
 #pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-                        acc[rb][t] = mma32<BF>(x[u & 1][t], w[u][rb], acc[rb][t]);
+                        for (int rb = 0; rb < RB; ++rb)
+                            acc[rb][t] = mma32<BF>(x[u & 1][t], w[u][rb], acc[rb][t]);
+                    }
+                }
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) w[u][rb] = load_w(s + CONV_PD, rb);
             }
@@ -269,11 +287,31 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     float* ep = reinterpret_cast<float*>(conv_smem + wave * CONV_SCRATCH);
     OutT* out = static_cast<OutT*>(a.out);
     const int32_t* rows_g = a.A.row_indices + (long)g * V;
+    if (SMALL) {
+        const long my_row = (long)rows_g[lane & 15] * a.osM;
+#pragma unroll
+        for (int t = 0; t < NTI; ++t) {
+            // accumulator register j of lane l: position 4*(l/16) + j, stored row l%16
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ep[(lane & 15) * 17 + 4 * (lane >> 4) + j] = acc16[t][j];
+            SHFLBW_WAVE_LDS_SYNC();
+            // the four 16-lane blocks take four stored rows per pass, one position each
+#pragma unroll
+            for (int i = 0; i < 16; i += 4) {
+                const int row = i + (lane >> 4);
+                const float v = ep[row * 17 + (lane & 15)];
+                const long ro = __shfl(my_row, row, 64);
+                if (live[t]) out[ro + ooff[t]] = (OutT)v;
+            }
+            SHFLBW_WAVE_LDS_SYNC();
+        }
+        return;
+    }
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const long my_row = (long)rows_g[rb * 32 + (lane & 31)] * a.osM;
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
+        for (int t = 0; t < NTI; ++t) {
             {
                 // accumulator register r of lane l: position 8*(r/4) + 4*(l/32) + r%4, stored row l%32
 #pragma unroll

@@ -48,6 +48,7 @@ struct shflbw_matrix {
     std::vector<int32_t> row_indices;  // M: original row of each stored row
     std::vector<int32_t> step_ptr;     // G+1: first k-step of each group
     std::vector<int32_t> kcount;       // G: kept columns per group (no padding)
+    int uniform_steps = -1;            // k-steps per group when all groups have the same number, else -1
     std::vector<int32_t> col_idx;      // steps*TK: ascending columns, -1 = padding
     bool slab_ok = false;              // windowed layout in use
     int slab_chunks = 0;               // C = ceil(K / SLAB_KC)

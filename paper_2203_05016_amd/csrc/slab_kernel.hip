@@ -95,6 +95,7 @@ struct SlabArgs {
     int n_tiles, gblocks;     // 128-column tiles, blocks of GW groups
     int gb_side;              // 0, or the group-block side of the blocks an XCD works on at a time (divides gblocks, and 32)
     int spin_limit;           // polls per bounded wait
+    int uniform_steps;        // k-steps of every group when they all have the same number, else -1
     int* status;              // set to non-zero by a wavefront whose wait ran out
 };
 
@@ -250,8 +251,11 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
         progress[wave] = C;  // nothing to read: never hold a stage back
         return;
     }
-    const int sbeg = a.A.step_ptr[g];
-    const int nsteps = a.A.step_ptr[g + 1] - sbeg;  // a multiple of PD
+    // the group's steps: without a memory access when every group has the same number (the
+    // first weights can then be requested at once instead of after a dependent scalar load)
+    const int sbeg = a.uniform_steps >= 0 ? g * a.uniform_steps : a.A.step_ptr[g];
+    const int nsteps = a.uniform_steps >= 0 ? a.uniform_steps : a.A.step_ptr[g + 1] - sbeg;  // a multiple of PD
+    const int first_chunk_g = a.first_chunk[g];   // wanted only when the first step is decoded
 
     floatx16 acc32[SMALL ? 1 : RB][SMALL ? 1 : NT];
     floatx4 acc16[SMALL ? NT : 1];
@@ -319,7 +323,7 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
         __builtin_amdgcn_sched_barrier(0);
     }
 
-    int chunk = a.first_chunk[g];   // of the step in hand, from the table's differences
+    int chunk = first_chunk_g;   // of the step in hand, from the table's differences
     int cur = 0;   // chunk last published; every step of an earlier chunk is done
     int seen = 0;  // chunks known to have landed (the least of the loaders' counts when last read)
     for (int s0 = 0; s0 < nsteps; s0 += PD) {

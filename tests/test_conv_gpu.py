@@ -111,6 +111,10 @@ def test_conv_1x1_nchw_one_launch_for_all_images(V, out_dtype):
     ("CHWN", 16, 8, 48, 48, 64, 64),    # batch innermost, boxes of 128, V = 64
     ("NCHW", 4, 8, 72, 72, 256, 128),   # V = 128: four row blocks, boxes of 64 at most
     ("CHWN", 24, 12, 9, 9, 128, 128),   # V = 128, batch innermost, one group
+    ("NCHW", 4, 8, 96, 96, 48, 16),     # V = 16 (16-position instruction tiles), boxes of 128, three groups share wavefronts
+    ("NCHW", 3, 24, 10, 10, 160, 16),   # V = 16, ten groups: two blocks of groups per box
+    ("CHWN", 40, 8, 6, 50, 16, 16),     # V = 16, batch innermost, one group
+    ("NCHW", 2, 150, 9, 9, 32, 16),     # V = 16, 1350 reduction indices: the koff list is refilled in bulks of 32 steps
 ])
 def test_conv_staged_kernel_box_shapes(layout, batch, Cin, H, Wd, Cout, V):
     announce("conv boxes", layout, batch, Cin, H, Wd, Cout, V)
@@ -141,11 +145,24 @@ def test_conv_infinite_weights_stay_in_their_group(kernel):
 
 
 def test_conv_staged_kernel_refuses_what_it_cannot_hold():
-    """Forcing the staged kernel on V = 16 is an error, not a silent switch."""
+    """Forcing the staged kernel on an input whose channels do not fit the LDS even for
+    the smallest box is an error, not a silent switch; the automatic choice takes the
+    gather kernel there."""
     announce("conv staged refusal")
-    p = synth.make_conv(2, 16, 7, 7, 32, 3, 3, 16, 0.5, seed=205, pad=(1, 1))
+    p = synth.make_conv(1, 4000, 5, 5, 32, 3, 3, 32, 0.9, seed=205, pad=(1, 1))
     with pytest.raises(binding.ShflbwError):
         _run_conv(p, kernel=2)
+    _parity(p)
+
+
+def test_conv_v16_staged_kernel_on_config4_shape():
+    """Config 4's tensor with groups of 16 output channels, every element, staged kernel
+    (automatic choice) and gather kernel."""
+    announce("config4 shape, V=16")
+    p = synth.config(3, V=16)
+    got = _parity(p)
+    assert binding.last_kernel().startswith("shflbw_conv_kernel<16,"), binding.last_kernel()
+    _parity(p, kernel=1)
 
 
 def test_config4_resnet_conv_full():
