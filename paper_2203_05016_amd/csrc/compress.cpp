@@ -182,6 +182,41 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
                 i = j;
             }
         };
+        // Pairs of full steps trade columns so that each gets its share of every residue class
+        // of the column index (mod 4; mod 8 for V = 16): arrange_step can then give every
+        // transposed read rows that fall into different bank groups, which a run of 16 random
+        // columns often cannot (seven columns of one class leave a read with two of them).  The
+        // lower columns of a class go to the first step of the pair; the pair is left alone where
+        // a new step would span more than the window.  c: the group's columns in step order
+        // (ascending on entry; afterwards ascending inside each step only).
+        auto balance_pairs = [&](std::vector<int32_t>& c, const std::vector<int>& lens) {
+            const int GS = (V == 16) ? 8 : 4;
+            size_t off = 0;
+            for (size_t st = 0; st + 1 < lens.size(); st += 2) {
+                const size_t n0 = (size_t)lens[st], n1 = (size_t)lens[st + 1];
+                if ((int)n0 == TK && (int)n1 == TK) {
+                    std::vector<int32_t> cls[8], a, b;
+                    for (size_t j = 0; j < n0 + n1; ++j) cls[c[off + j] & (GS - 1)].push_back(c[off + j]);
+                    int take[8], total = 0;
+                    for (int k = 0; k < GS; ++k) { take[k] = (int)cls[k].size() / 2; total += take[k]; }
+                    for (int k = 0; k < GS && total < TK; ++k)
+                        if (cls[k].size() & 1) { ++take[k]; ++total; }
+                    for (int k = 0; k < GS; ++k)
+                        for (size_t j = 0; j < cls[k].size(); ++j) ((int)j < take[k] ? a : b).push_back(cls[k][j]);
+                    std::sort(a.begin(), a.end());
+                    std::sort(b.begin(), b.end());
+                    if (a.back() / shflbw::SLAB_KC > b.back() / shflbw::SLAB_KC) a.swap(b);   // chunks must not decrease
+                    auto fits = [&](const std::vector<int32_t>& v) {
+                        return v.back() / shflbw::SLAB_KC - v.front() / shflbw::SLAB_KC < shflbw::SLAB_WINDOW;
+                    };
+                    if ((int)a.size() == TK && (int)b.size() == TK && fits(a) && fits(b)) {
+                        std::copy(a.begin(), a.end(), c.begin() + off);
+                        std::copy(b.begin(), b.end(), c.begin() + off + n0);
+                    }
+                }
+                off += n0 + n1;
+            }
+        };
         // The slab kernel learns a step's chunk from a 4-bit difference to the step
         // before it (the group's first chunk is stored per group), so where two
         // consecutive steps of the windowed layout lie more than 15 chunks apart,
@@ -192,7 +227,7 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
             int prev = -1;
             for (int len : lens) {
                 t += (size_t)len;
-                const int e = c[t - 1] / shflbw::SLAB_KC;
+                const int e = *std::max_element(c.begin() + (t - len), c.begin() + t) / shflbw::SLAB_KC;
                 if (prev >= 0)
                     while (e - prev > shflbw::SLAB_MAX_CHUNK_STEP) {
                         prev += shflbw::SLAB_MAX_CHUNK_STEP;
@@ -207,17 +242,20 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
             chunk.swap(out_chunk);
         };
         std::vector<std::vector<int>> plain(G), win(G), win_chunk(G);
+        std::vector<std::vector<int32_t>> wcols(cols);   // the columns in the step order of the windowed layout
         size_t n_plain = 0, n_win = 0;
         for (int g = 0; g < G; ++g) {
             cut(cols[g], false, plain[g]);
             cut(cols[g], true, win[g]);
-            bridge_gaps(cols[g], win[g], win_chunk[g]);
+            balance_pairs(wcols[g], win[g]);
+            bridge_gaps(wcols[g], win[g], win_chunk[g]);
             n_plain += plain[g].size();
             n_win += win[g].size();
         }
         A->slab_chunks = (K + shflbw::SLAB_KC - 1) / shflbw::SLAB_KC;
         A->slab_ok = n_plain > 0 && (double)n_win <= 1.15 * (double)n_plain;
         const std::vector<std::vector<int>>& lens = A->slab_ok ? win : plain;
+        const std::vector<std::vector<int32_t>>& scols = A->slab_ok ? wcols : cols;   // columns in step order
 
         // In the windowed layout every group gets a multiple of SLAB_UNROLL steps
         // (the slab kernel runs its steps in unrolled batches); the extra steps are
@@ -247,9 +285,9 @@ int shflbw_compress(const void* W, int ldw, const uint8_t* mask, const int32_t* 
             for (int len : lens[g]) {
                 uint16_t* dst = &A->values[step * (size_t)V * TK];
                 int slot_of[32];
-                arrange_step(&cols[g][t], len, V, slot_of);
+                arrange_step(&scols[g][t], len, V, slot_of);
                 for (int j = 0; j < len; ++j, ++t) {
-                    const int k = cols[g][t];
+                    const int k = scols[g][t];
                     A->col_idx[step * TK + slot_of[j]] = k;
                     for (int i = 0; i < V; ++i)
                         dst[value_slot(V, i, slot_of[j])] = Wb[(size_t)rows[i] * ldw + k];
