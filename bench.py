@@ -33,8 +33,8 @@ HBM_PEAK = 8.0e12
 # kernel choice, no tile override, and the kernel named in COUNTER_KERNEL.
 COUNTER_SOURCE = "profiles/slab_kernel_ffn_config2_pmc.md"
 COUNTER_KERNEL = "shflbw_slab_kernel<32,12,f16,f16 out>"
-L2_TO_CU_BYTES = 334.0e6        # TCP_TCC_READ_REQ x 128 B per launch
-MEASURED_TRAFFIC_BYTES = 109.2e6  # FETCH_SIZE + WRITE_SIZE per launch, scaled by the same counters on a 64 MiB copy
+L2_TO_CU_BYTES = 330.0e6        # TCP_TCC_READ_REQ x 128 B per launch
+MEASURED_TRAFFIC_BYTES = 109.1e6  # FETCH_SIZE + WRITE_SIZE per launch, scaled by the same counters on a 64 MiB copy
 PAPER_CONTEXT = "paper: up to 1.81x/4.18x/1.90x over cuBLAS dense at 75% on V100/T4/A100 (context only)"
 
 
@@ -323,6 +323,31 @@ def measure_l2_stream(p):
     return out
 
 
+def measure_lds_read():
+    """The probe library's LDS read rates over the chip: the transposing 16-bit read the slab
+    kernel's matrix instructions are fed with, and a plain read of the same width, twelve
+    wavefronts per CU (the slab kernel's compute wavefronts)."""
+    import ctypes
+    import torch
+    lib = ctypes.CDLL(PROBE_LIB if os.path.exists(PROBE_LIB) else build_probe())
+    fn = lib.shflbw_probe_lds_read
+    fn.restype = ctypes.c_longlong
+    fn.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    out = {}
+    for name, tr in (("transposing_ds_read_b64_tr_b16", 1), ("plain_ds_read_b64", 0)):
+        state = {"bytes": 0}
+
+        def step():
+            state["bytes"] = fn(tr, 12, 500, ctypes.c_void_p(sink.data_ptr()), stream)
+            assert state["bytes"] > 0
+        ms = time_steps(step, 10, 2)
+        out[name] = {"ms": ms, "TBps": state["bytes"] / (ms * 1e-3) / 1e12,
+                     "bytes_per_clock_per_cu_at_2.4GHz": state["bytes"] / (ms * 1e-3) / 256 / 2.4e9}
+    return out
+
+
 def check_sample(p, rows, samples):
     """The rows `rows` of every output buffer the timed launches wrote, against the oracle
     (element-wise, the parity tests' bound)."""
@@ -442,6 +467,7 @@ def main():
         l2_r["kernel_l2_bytes_source"] = COUNTER_SOURCE
         l2_r["kernel_l2_GBps"] = L2_TO_CU_BYTES / (main_r["ms"] * 1e-3) / 1e9
         l2_r["frac_of_hot_stream"] = l2_r["kernel_l2_GBps"] / l2_r["hot"]["GBps"]
+    lds_r = measure_lds_read()
     lib_r = measure_library_gemm(p, args.steps, args.warmup)
     lib_r["sparse_speedup_over_library_dense"] = lib_r["ms"] / main_r["ms"]
 
@@ -516,6 +542,7 @@ def main():
         "bf16_operands": {"ms": bf16_r["ms"], "tflops": bf16_r["tflops"]},
         "layernorm_transpose": ln_r,
         "l2_stream_probe": l2_r,
+        "lds_read_probe": lds_r,
         "library_dense_gemm": lib_r,
         "cpu_baseline": cpu,
         "context": PAPER_CONTEXT,

@@ -72,9 +72,56 @@ __global__ __launch_bounds__(64 * PROBE_LOADERS) void l2_stream_kernel(
     if (threadIdx.x == 0 && *(volatile float*)(smem + 4 * (wg & 63)) == 12345.678f) sink[0] = 1.f;
 }
 
+// LDS read rate: every wavefront issues batches of eight independent 8-byte-per-lane reads at
+// conflict-free addresses, transposing (ds_read_b64_tr_b16, what the slab kernel feeds its
+// matrix instructions with) or plain (ds_read_b64).
+typedef short probe_short4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) probe_short4* probe_lds_short4_ptr;
+template <bool TRANSPOSING>
+__global__ __launch_bounds__(1024) void lds_read_kernel(int iters, float* sink)
+{
+    __shared__ __attribute__((aligned(1024))) char smem[64 * 1024];
+    for (int i = threadIdx.x; i < 64 * 1024 / 4; i += blockDim.x) reinterpret_cast<int*>(smem)[i] = i;
+    __syncthreads();
+    const unsigned base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem + (threadIdx.x & 63) * 8;
+    typedef unsigned probe_uint2 __attribute__((ext_vector_type(2)));
+    unsigned acc = 0;
+    // The reads are volatile assembly so that the compiler neither merges reads of equal addresses
+    // across iterations nor moves them; the wait names the results so that their uses stay behind it.
+    for (int it = 0; it < iters; ++it) {
+        const unsigned a = base + (it & 3) * 16384;
+        probe_uint2 v0, v1, v2, v3, v4, v5, v6, v7;
+#define PROBE_READ(V, OFF)                                                                              \
+        if (TRANSPOSING) asm volatile("ds_read_b64_tr_b16 %0, %1 offset:" #OFF : "=v"(V) : "v"(a));       \
+        else asm volatile("ds_read_b64 %0, %1 offset:" #OFF : "=v"(V) : "v"(a));
+        PROBE_READ(v0, 0) PROBE_READ(v1, 2048) PROBE_READ(v2, 4096) PROBE_READ(v3, 6144)
+        PROBE_READ(v4, 8192) PROBE_READ(v5, 10240) PROBE_READ(v6, 12288) PROBE_READ(v7, 14336)
+#undef PROBE_READ
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(v0), "+v"(v1), "+v"(v2), "+v"(v3), "+v"(v4), "+v"(v5), "+v"(v6), "+v"(v7));
+        acc ^= v0[0] ^ v1[1] ^ v2[0] ^ v3[1] ^ v4[0] ^ v5[1] ^ v6[0] ^ v7[1];
+    }
+    if (acc == 0x12345678u) sink[0] = 1.f;
+}
+
 }  // namespace
 
 extern "C" {
+
+/* 256 workgroups of `waves` wavefronts each read `iters` x 8 x 512 bytes of LDS per wavefront, with
+ * the transposing 16-bit read (transposing != 0) or the plain 8-byte read.  Enqueues on `stream`;
+ * returns the bytes read over the chip, or a negative value on bad arguments. */
+long long shflbw_probe_lds_read(int transposing, int waves, int iters, void* sink, void* stream)
+{
+    if (!sink || waves < 1 || waves > 16 || iters < 1) return -1;
+    if (transposing)
+        hipLaunchKernelGGL(lds_read_kernel<true>, dim3(256), dim3(64 * waves), 0, static_cast<hipStream_t>(stream), iters, static_cast<float*>(sink));
+    else
+        hipLaunchKernelGGL(lds_read_kernel<false>, dim3(256), dim3(64 * waves), 0, static_cast<hipStream_t>(stream), iters, static_cast<float*>(sink));
+    if (hipGetLastError() != hipSuccess) return -2;
+    return 256LL * waves * iters * 8 * 512;
+}
+
 
 /* Streams K x 128-column slabs of the row-major 16-bit matrix X (K x N, leading dimension
  * ldx, device memory) into LDS.  mode 0: 256 workgroups over the first 64 slabs, `passes` times.
