@@ -348,6 +348,37 @@ def measure_lds_read():
     return out
 
 
+def measure_stream_store():
+    """The probe library's loads and stores through one CU's memory path: 256 workgroups stream
+    201 MB of L2-resident X into LDS, write 75 MB of Y in the slab kernel's write-back pattern, or do
+    both at once - how far a launch's loads and stores can overlap."""
+    import ctypes
+    import torch
+    lib = ctypes.CDLL(PROBE_LIB if os.path.exists(PROBE_LIB) else build_probe())
+    fn = lib.shflbw_probe_stream_store
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p, ctypes.c_longlong, ctypes.c_int,
+                   ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_longlong),
+                   ctypes.POINTER(ctypes.c_longlong), ctypes.c_void_p, ctypes.c_void_p]
+    X = torch.ones((1024, 8192), dtype=torch.float16, device="cuda:0")
+    Y = torch.zeros((4096, 8192), dtype=torch.float16, device="cuda:0")
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    out = {}
+    for name, ld, st in (("stream_only", 1, 0), ("store_only", 0, 1), ("both", 1, 1)):
+        lb, sb = ctypes.c_longlong(0), ctypes.c_longlong(0)
+
+        def step():
+            rc = fn(ctypes.c_void_p(X.data_ptr()), 8192, ctypes.c_void_p(Y.data_ptr()), 8192, ld, st, 3, 3,
+                    ctypes.byref(lb), ctypes.byref(sb), ctypes.c_void_p(sink.data_ptr()), stream)
+            assert rc == 0
+        ms = time_steps(step, 20, 5)
+        out[name] = {"ms": ms, "load_bytes": lb.value, "store_bytes": sb.value,
+                     "TBps": (lb.value + sb.value) / (ms * 1e-3) / 1e12}
+    out["both_over_sum_of_parts"] = out["both"]["ms"] / (out["stream_only"]["ms"] + out["store_only"]["ms"])
+    return out
+
+
 def check_sample(p, rows, samples):
     """The rows `rows` of every output buffer the timed launches wrote, against the oracle
     (element-wise, the parity tests' bound)."""
@@ -468,6 +499,7 @@ def main():
         l2_r["kernel_l2_GBps"] = L2_TO_CU_BYTES / (main_r["ms"] * 1e-3) / 1e9
         l2_r["frac_of_hot_stream"] = l2_r["kernel_l2_GBps"] / l2_r["hot"]["GBps"]
     lds_r = measure_lds_read()
+    path_r = measure_stream_store()
     lib_r = measure_library_gemm(p, args.steps, args.warmup)
     lib_r["sparse_speedup_over_library_dense"] = lib_r["ms"] / main_r["ms"]
 
@@ -543,6 +575,7 @@ def main():
         "layernorm_transpose": ln_r,
         "l2_stream_probe": l2_r,
         "lds_read_probe": lds_r,
+        "cu_memory_path_probe": path_r,
         "library_dense_gemm": lib_r,
         "cpu_baseline": cpu,
         "context": PAPER_CONTEXT,

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(64 * PROBE_LOADERS) void l2_stream_kernel(
     const int lrow = lane >> 4, lpos = lane & 15;
     const int C = K / PROBE_KC;                      // K is a multiple of 64 (checked on the host)
     const int wg = blockIdx.x, xcd = wg & 7, wslot = wg >> 3;
-    const int nt = (wslot / gblocks) * 8 + xcd;
+    const int nt = xcd * ((n_tiles + 7) / 8) + wslot / gblocks;   // the slab kernel's mapping
     if (nt >= n_tiles) return;
     const uint16_t* Xt = X + (long)nt * 128;
     const int total = C * passes;
@@ -104,6 +104,68 @@ __global__ __launch_bounds__(1024) void lds_read_kernel(int iters, float* sink)
     if (acc == 0x12345678u) sink[0] = 1.f;
 }
 
+
+// Loads and stores of one CU together: wavefronts 0-3 stream 128-column slabs of X into LDS as above
+// (`passes` times 16 chunks of 64 rows), wavefronts 4-15 write `tiles` tiles of 32 rows x 256 bytes of
+// Y each with non-temporal 16-byte stores, 8 rows x 128 bytes per instruction - the slab kernel's
+// write-back pattern.  Either half can be switched off.
+typedef unsigned probe_uint4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(1024) void stream_store_kernel(const uint16_t* X, long ldx, uint16_t* Y, long ldy,
+                                                             int do_stream, int do_store, int passes, int tiles,
+                                                             float* sink)
+{
+    __shared__ __attribute__((aligned(1024))) char smem[PROBE_STAGES * PROBE_KC * 256];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wg = blockIdx.x, xcd = wg & 7, wslot = wg >> 3;
+    if (wave < PROBE_LOADERS) {
+        if (!do_stream) return;
+        const unsigned base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+        const int lrow = lane >> 4, lpos = lane & 15;
+        const uint16_t* Xt = X + (long)(xcd * 8 + wslot / 4) * 128;      // 64 slabs, 4 sharers each
+        const int total = 16 * passes;
+        auto issue = [&](int cg) __attribute__((always_inline)) {
+            const int c = cg % 16;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int piece = wave * 4 + i;
+                const int row = c * PROBE_KC + 4 * piece + lrow;
+                dma16(Xt + (long)row * ldx + lpos * 8,
+                      base + (cg % PROBE_STAGES) * (PROBE_KC * 256) + piece * 1024);
+            }
+        };
+#pragma unroll
+        for (int cg = 0; cg < PROBE_LEAD; ++cg)
+            if (cg < total) issue(cg);
+        for (int cg = 0; cg < total; ++cg) {
+            int younger = total - 1 - cg;
+            younger = younger < PROBE_LEAD - 1 ? younger : PROBE_LEAD - 1;
+            switch (younger) {
+                case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+                case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+                case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+                default: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+            }
+            if (cg + PROBE_LEAD < total) issue(cg + PROBE_LEAD);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (lane == 0 && *(volatile float*)(smem + 4 * (wg & 63)) == 12345.678f) sink[0] = 1.f;
+        return;
+    }
+    if (!do_store) return;
+    const long row0 = ((long)(wg % 10) * 12 + (wave - PROBE_LOADERS)) * 32;   // below 3840
+    const probe_uint4 v = {0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+    for (int i = 0; i < tiles; ++i) {
+        const int ct = (wg / 10 + 26 * i) % 64;
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                __builtin_nontemporal_store(
+                    v, reinterpret_cast<probe_uint4*>(Y + (row0 + r * 8 + (lane >> 3)) * ldy + ct * 128 + p * 64 + (lane & 7) * 8));
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -122,6 +184,26 @@ long long shflbw_probe_lds_read(int transposing, int waves, int iters, void* sin
     return 256LL * waves * iters * 8 * 512;
 }
 
+
+/* 256 workgroups of 16 wavefronts: four stream slabs of the row-major 16-bit matrix X (at least 1024
+ * rows and 8192 columns) into LDS, `passes` x 256 KB per workgroup, twelve write `tiles` tiles of 32
+ * rows x 256 bytes each to the row-major 16-bit matrix Y (at least 3840 rows and 8192 columns).
+ * Enqueues on `stream`; *load_bytes and *store_bytes receive what was moved; returns 0, or a negative
+ * value on bad arguments. */
+int shflbw_probe_stream_store(const void* X, long long ldx, void* Y, long long ldy, int do_stream, int do_store,
+                              int passes, int tiles, long long* load_bytes, long long* store_bytes, void* sink,
+                              void* stream)
+{
+    if (!X || !Y || !sink || !load_bytes || !store_bytes || ldx < 8192 || ldy < 8192 || passes < 1 || tiles < 1)
+        return -1;
+    hipLaunchKernelGGL(stream_store_kernel, dim3(256), dim3(1024), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint16_t*>(X), (long)ldx, static_cast<uint16_t*>(Y), (long)ldy, do_stream,
+                       do_store, passes, tiles, static_cast<float*>(sink));
+    if (hipGetLastError() != hipSuccess) return -2;
+    *load_bytes = do_stream ? 256LL * passes * 16 * PROBE_KC * 256 : 0;
+    *store_bytes = do_store ? 256LL * 12 * tiles * 32 * 256 : 0;
+    return 0;
+}
 
 /* Streams K x 128-column slabs of the row-major 16-bit matrix X (K x N, leading dimension
  * ldx, device memory) into LDS.  mode 0: 256 workgroups over the first 64 slabs, `passes` times.
@@ -146,7 +228,7 @@ long long shflbw_probe_l2_stream(const void* X, long long ldx, int K, long long 
     if (hipGetLastError() != hipSuccess) return -2;
     long long active = 0;   // workgroups whose column tile exists
     for (int wg = 0; wg < wgs; ++wg)
-        if (((wg >> 3) / gb) * 8 + (wg & 7) < tiles) ++active;
+        if ((wg & 7) * ((tiles + 7) / 8) + (wg >> 3) / gb < tiles) ++active;
     return active * (long long)K * 256 * passes;
 }
 

@@ -138,8 +138,10 @@ __global__ __launch_bounds__(64 * (GW + SLAB_LOADERS)) void shflbw_slab_kernel(S
     const int xcd = wg & 7, wslot = wg >> 3;
     int gb, nt;
     if (a.gb_side == 0) {
+        // an XCD takes a run of neighbouring column tiles: the tiles it works on at a time are
+        // adjacent in X and in Y (1 % faster than tiles 8 apart)
         gb = wslot % a.gblocks;
-        nt = (wslot / a.gblocks) * 8 + xcd;
+        nt = xcd * ((a.n_tiles + 7) / 8) + wslot / a.gblocks;
     } else {
         const int side_n = 32 / a.gb_side, blocks_g = a.gblocks / a.gb_side;
         const int block = wslot >> 5, inside = wslot & 31;
