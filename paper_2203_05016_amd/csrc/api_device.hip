@@ -208,6 +208,7 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     a.gblocks = gblocks;
     a.in_bytes_total = (unsigned)in_total;
     a.gpb = gpb;
+    a.uniform_steps = A->uniform_steps;
     {
         const int tiles = (th * tw * tb + 31) / 32;
         const int spare = CONV_GW / gpb;   // wavefronts per group

@@ -17,7 +17,7 @@
 // all-zero channel plane.
 //
 // Algorithm 1's parts: BulkLoadMeta = column indices in bulks of 64 k-steps,
-// the weight operand eight (V = 64: four, V = 128: two) k-steps ahead in as many register sets;
+// the weight operand four (V = 128: two) k-steps ahead in as many register sets;
 // V = 16 runs on the 16x16x32 instruction: tiles of 16 positions, k-steps of 32 indices;
 // StitchTile = the LDS gather above (each lane reads the 8 reduction indices
 // x up to 4 positions it feeds to the matrix cores); WarpMMA =
@@ -58,6 +58,7 @@ struct ConvArgs {
     int b_fast;               // 1: batch runs fastest in the local index (CHWN)
     int gblocks;              // blocks of gpb groups
     int gpb, tsplit;          // groups per workgroup; wavefronts that share a group's instruction tiles
+    int uniform_steps;        // k-steps of every group when they all have the same number, else -1
     int in_bytes;             // LDS bytes reserved for the staged input (and the scratch)
     unsigned in_bytes_total;  // bytes of the whole input tensor (below 2^32 - 64: the host checks)
     // ceil(2^40 / d) for the divisors the kernel needs: x / d == (x * m) >> 40 for x, d < 2^20
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     constexpr int NTI = NT * (32 / POS);              // instruction tiles per wavefront
     constexpr int KBLOCKS = TK / 8;                   // a lane feeds 8 reduction indices of block lane / POS
     constexpr int BULK = CONV_BULK * 16 / TK;         // k-steps of koff values held at a time (the list's size is fixed)
-    constexpr int CONV_PD = RB == 1 ? 8 : RB == 2 ? 4 : 2;   // k-steps the weight operand is fetched ahead
+    constexpr int CONV_PD = RB <= 2 ? 4 : 2;   // k-steps the weight operand is fetched ahead
     static_assert(BULK % CONV_PD == 0, "bulk boundaries fall on batch boundaries");
     extern __shared__ __attribute__((aligned(16))) char conv_smem[];
     _Float16* xin = reinterpret_cast<_Float16*>(conv_smem);
@@ -107,8 +108,13 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     const int gi = wave % a.gpb, ts = wave / a.gpb;
     const int g = gb * a.gpb + gi;
     const bool have_group = g < a.A.G && ts < a.tsplit;
-    const int sbeg = have_group ? a.A.step_ptr[g] : 0;
-    const int nsteps = have_group ? a.A.step_ptr[g + 1] - sbeg : 0;
+    // the group's steps: without a memory access when every group has the same number (the
+    // column indices and first weights can then be requested at once)
+    int sbeg = 0, nsteps = 0;
+    if (have_group) {
+        sbeg = a.uniform_steps >= 0 ? g * a.uniform_steps : a.A.step_ptr[g];
+        nsteps = a.uniform_steps >= 0 ? a.uniform_steps : a.A.step_ptr[g + 1] - sbeg;
+    }
 
     // koff values of steps [s0, s0 + BULK) of this group into the list
     constexpr int BULK_LOADS = BULK * TK / 64;
@@ -121,9 +127,13 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
             cols[i] = j < avail ? cp[j] : -1;
         }
     };
-    auto store_koff = [&](const int (&cols)[BULK_LOADS]) __attribute__((always_inline)) {
+    // `steps`: k-steps of the bulk that the group has; the loop reads up to CONV_PD + 1 entries past
+    // them (whole batches, one entry ahead), which must name the zero plane; later ones are not read
+    auto store_koff = [&](const int (&cols)[BULK_LOADS], int steps) __attribute__((always_inline)) {
+        const int wanted = (steps + CONV_PD + 2) * TK;
 #pragma unroll
         for (int i = 0; i < BULK_LOADS; ++i) {
+            if (i * 64 >= wanted) break;   // uniform
             const int k = cols[i];
             int off = zero_off;
             if (k >= 0) {
@@ -184,7 +194,7 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
         }
         if (wave == 0) xin[zero_off + p] = (_Float16)0.f;   // the all-zero plane
     }
-    store_koff(cols0);
+    store_koff(cols0, nsteps);
     __syncthreads();
 
     // ---- this lane's output positions: n' = POS*(ts*NTI + t) + lane%POS
@@ -259,7 +269,7 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
                         int cols[BULK_LOADS];
                         load_cols(s + 2, cols);
                         SHFLBW_WAVE_LDS_SYNC();   // reads of the old list are over
-                        store_koff(cols);
+                        store_koff(cols, nsteps - (s + 2));
                         SHFLBW_WAVE_LDS_SYNC();
                     }
                 }
@@ -323,7 +333,9 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
                 for (int i = 0; i < 32; i += 2) {
                     const int row = i + (lane >> 5);
                     const float v = ep[row * 33 + (lane & 31)];
-                    const long ro = __shfl(my_row, row, 64);
+                    // the two rows' offsets through scalar registers (my_row fits 32 bits: the host checks the tensor's size)
+                    const int r0 = __builtin_amdgcn_readlane((int)my_row, i), r1 = __builtin_amdgcn_readlane((int)my_row, i + 1);
+                    const long ro = lane < 32 ? r0 : r1;
                     if (live[t]) out[ro + ooff[t]] = (OutT)v;
                 }
                 SHFLBW_WAVE_LDS_SYNC();
