@@ -12,7 +12,7 @@
 // and column) and noff only on the output position (its top-left input
 // element inside the box).  Each wavefront turns the column indices of its
 // group into koff values 64 k-steps at a time and keeps them in a private LDS
-// list (one 16-byte read per lane and step in the loop); noff lives in
+// list of byte offsets (two 16-byte reads per lane and step in the loop, no unpacking); noff lives in
 // registers.  A padded slot of a k-step (column index -1) points at an extra
 // all-zero channel plane.
 //
@@ -43,7 +43,7 @@ constexpr int CONV_GW = 8;             // compute wavefronts (row groups) per wo
 constexpr int CONV_TN = 128;           // most output positions per workgroup
 constexpr int CONV_SCRATCH = 32 * 33 * 4;  // write-back scratch of one wavefront (fp32, pitch 33)
 constexpr int CONV_BULK = 64;          // k-steps of koff values a wavefront holds at a time
-constexpr int CONV_LIST_BYTES = CONV_GW * CONV_BULK * 16 * 2;
+constexpr int CONV_LIST_BYTES = CONV_GW * CONV_BULK * 16 * 4;   // byte offsets as 32-bit words: no unpacking in the loop
 
 struct ConvArgs {
     PackedView A;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // this wavefront's list of koff values: CONV_BULK steps x 16 slots
-    uint16_t* klist = reinterpret_cast<uint16_t*>(conv_smem + a.in_bytes) + wave * (CONV_BULK * 16);
+    uint32_t* klist = reinterpret_cast<uint32_t*>(conv_smem + a.in_bytes) + wave * (CONV_BULK * 16);
 
     // which box, which block of groups
     int box = blockIdx.x / a.gblocks;
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
                 const int r = conv_div(rs, a.m_S), sx = rs - r * a.S;
                 off = c * plane + (r * a.cols_in + sx) * a.tb;
             }
-            klist[i * 64 + lane] = (uint16_t)off;
+            klist[i * 64 + lane] = (uint32_t)off * 2u;
         }
     };
     int cols0[BULK_LOADS];
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
         }
         const int b = b0 + bb, y = y0 + yy, x = x0 + xx;
         live[t] = n < npos && b < a.B && y < a.Ho && x < a.Wo;
-        noff[t] = live[t] ? (yy * a.sh * a.cols_in + xx * a.sw) * a.tb + bb : 0;
+        noff[t] = live[t] ? 2 * ((yy * a.sh * a.cols_in + xx * a.sw) * a.tb + bb) : 0;   // in bytes
         ooff[t] = live[t] ? (int)(b * a.osB + y * a.osH + x * a.osW) : 0;
     }
 
@@ -234,8 +234,8 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
 
     if (nsteps > 0) {
         const int kblock = lane / POS;
-        typedef unsigned short ushort8 __attribute__((ext_vector_type(8)));
-        const ushort8* kl = reinterpret_cast<const ushort8*>(klist) + kblock;   // 8 slots of this lane's block
+        typedef unsigned uint8v __attribute__((ext_vector_type(8)));
+        const uint8v* kl = reinterpret_cast<const uint8v*>(klist) + kblock;   // 8 slots of this lane's block
 
         // StitchTile of one step: 8 reduction indices x up to NT positions per lane.  The
         // list entry of a step is read one step before its gathers go out, the gathers one
@@ -245,17 +245,23 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
         // plane (the list's filler), and every load is unconditional, which keeps the
         // register sets static and the wait counts exact.
         auto read_list = [&](int s) __attribute__((always_inline)) { return kl[(s & (BULK - 1)) * KBLOCKS]; };
-        auto gather = [&](const ushort8& ko, half8 (&x)[NTI]) __attribute__((always_inline)) {
+        static_assert(CONV_PD % 2 == 0, "entries and tiles alternate between two register sets");
+        // Order inside a step (pinned, or the scheduler moves a step's gathers next to their use and
+        // every step waits for two LDS round trips): the halves gathered a step ago become this
+        // step's operand; the products go out; the next step's gathers go out, then the list entry of
+        // the step after that, then the refill of this step's weight registers.  LDS results come
+        // back in order, so the only wait a step has is for gathers that had a whole step to land.
+        uint8v ko[2];                       // list entry of step j in ko[j & 1]
+        unsigned short raw[2][NTI][8];       // gathered halves of step j in raw[j & 1]
+        auto gather_raw = [&](const uint8v& e8, unsigned short (&r)[NTI][8]) __attribute__((always_inline)) {
 #pragma unroll
             for (int t = 0; t < NTI; ++t)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) x[t][e] = xin[(int)ko[e] + noff[t]];
+                for (int e = 0; e < 8; ++e)
+                    r[t][e] = *reinterpret_cast<const unsigned short*>(reinterpret_cast<const char*>(xin) + (e8[e] + (unsigned)noff[t]));
         };
-        static_assert(CONV_PD % 2 == 0, "entries and tiles alternate between two register sets");
-        ushort8 ko[2];      // list entry of step j in ko[j & 1]
-        half8 x[2][NTI];    // gathered tile of step j in x[j & 1]
         ko[0] = read_list(0);
-        gather(ko[0], x[0]);
+        gather_raw(ko[0], raw[0]);
         ko[1] = read_list(1);
         const int nsteps_r = (nsteps + CONV_PD - 1) / CONV_PD * CONV_PD;
         for (int s0 = 0; s0 < nsteps_r; s0 += CONV_PD) {
@@ -273,20 +279,31 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
                         SHFLBW_WAVE_LDS_SYNC();
                     }
                 }
-                gather(ko[(u + 1) & 1], x[(u + 1) & 1]);   // step s + 1, in flight while step s is multiplied
-                ko[u & 1] = read_list(s + 2);
+                half8 x[NTI];
+#pragma unroll
+                for (int t = 0; t < NTI; ++t) {
+                    typedef unsigned short us8 __attribute__((ext_vector_type(8)));
+                    const us8 v = {raw[u & 1][t][0], raw[u & 1][t][1], raw[u & 1][t][2], raw[u & 1][t][3],
+                                   raw[u & 1][t][4], raw[u & 1][t][5], raw[u & 1][t][6], raw[u & 1][t][7]};
+                    x[t] = __builtin_bit_cast(half8, v);
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int t = 0; t < NTI; ++t) {
                     if (SMALL) {
-                        acc16[t] = mma16<BF>(x[u & 1][t], w[u][0], acc16[t]);
+                        acc16[t] = mma16<BF>(x[t], w[u][0], acc16[t]);
                     } else {
 #pragma unroll
                         for (int rb = 0; rb < RB; ++rb)
-                            acc[rb][t] = mma32<BF>(x[u & 1][t], w[u][rb], acc[rb][t]);
+                            acc[rb][t] = mma32<BF>(x[t], w[u][rb], acc[rb][t]);
                     }
                 }
+                gather_raw(ko[(u + 1) & 1], raw[(u + 1) & 1]);   // step s + 1
+                __builtin_amdgcn_sched_barrier(0);
+                ko[u & 1] = read_list(s + 2);
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) w[u][rb] = load_w(s + CONV_PD, rb);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
