@@ -145,8 +145,32 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     const size_t lds_cap = 160 * 1024 - 512;
     const double kg_avg = A->G > 0 ? (double)A->nnz / ((double)A->V * A->G) : 0.0;
     const double groups_per_box = A->G < CONV_GW ? A->G : CONV_GW;
+    // Staging with 4-byte loads wants pairs of elements that are neighbours in memory, 4-byte
+    // aligned, and inside or outside the image together.  NCHW: pairs along x - an even image
+    // width, boxes that start at even x (tw * sw even), the staged box widened by one column on the
+    // left when the padding is odd, and an even staged row pitch.  CHWN: pairs along the batch - an
+    // even batch and an even number of images per box.
+    // It is asked for when it needs at most 0.7 of the load instructions of 2-byte staging (a
+    // wavefront covers 64 elements of a channel per instruction there; with pairs it covers 64
+    // pairs, or several channels when a channel has 32 pairs or fewer).
+    auto pair_cols = [&](int tw) {
+        size_t cols = (size_t)(tw - 1) * sw + S;
+        if (!chwn) cols = (cols + (pw & 1) + 1) / 2 * 2;
+        return cols;
+    };
+    auto pairs_ok = [&](int th, int tw, int tb) {
+        if (!(chwn ? (B % 2 == 0 && tb % 2 == 0) : (W % 2 == 0 && (tw * sw) % 2 == 0))) return false;
+        const size_t rows = (size_t)(th - 1) * sh + R;
+        const size_t plane1 = rows * ((size_t)(tw - 1) * sw + S) * tb, plane2 = rows * pair_cols(tw) * tb / 2;
+        const size_t lpp = plane2 <= 8 ? 8 : plane2 <= 16 ? 16 : plane2 <= 32 ? 32 : 64;
+        const double n1 = (double)((plane1 + 63) / 64), n2 = (double)((plane2 + lpp - 1) / lpp) * (double)lpp / 64.0;
+        return n2 <= 0.7 * n1;
+    };
+    auto staged_cols = [&](int th, int tw, int tb) {
+        return pairs_ok(th, tw, tb) ? pair_cols(tw) : (size_t)(tw - 1) * sw + S;
+    };
     auto staged_elems = [&](int th, int tw, int tb) {
-        return ((size_t)C + 1) * ((size_t)(th - 1) * sh + R) * ((size_t)(tw - 1) * sw + S) * tb;
+        return ((size_t)C + 1) * ((size_t)(th - 1) * sh + R) * staged_cols(th, tw, tb) * tb;
     };
     auto fits = [&](int th, int tw, int tb) {
         const size_t e = staged_elems(th, tw, tb);
@@ -203,7 +227,9 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     }
     a.th = th; a.tw = tw; a.tb = tb;
     a.ny = (Ho + th - 1) / th; a.nx = (Wo + tw - 1) / tw; a.nb = (B + tb - 1) / tb;
-    a.rows_in = (th - 1) * sh + R; a.cols_in = (tw - 1) * sw + S;
+    a.rows_in = (th - 1) * sh + R; a.cols_in = (int)staged_cols(th, tw, tb);
+    a.stage_pairs = pairs_ok(th, tw, tb) ? 1 : 0;
+    a.dx = (!chwn && a.stage_pairs) ? (pw & 1) : 0;
     a.b_fast = chwn ? 1 : 0;
     a.gblocks = gblocks;
     a.in_bytes_total = (unsigned)in_total;
@@ -218,6 +244,7 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     auto magic = [](int d) { return (((unsigned long long)1 << 40) + d - 1) / (unsigned long long)d; };
     a.m_RS = magic(R * S); a.m_S = magic(S); a.m_tb = magic(tb); a.m_cols_in = magic(a.cols_in);
     a.m_tw = magic(tw); a.m_th = magic(th);
+    a.m_cols2 = magic(a.cols_in / 2 > 0 ? a.cols_in / 2 : 1); a.m_tb2 = magic(tb / 2 > 0 ? tb / 2 : 1);
     size_t in_bytes = (staged_elems(th, tw, tb) * 2 + 15) / 16 * 16;
     const size_t scratch = (size_t)CONV_GW * CONV_SCRATCH;
     if (in_bytes < scratch) in_bytes = scratch;
@@ -226,9 +253,11 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     return true;
 }
 
-template <int V, int NT, typename OutT, bool BF>
+template <int V, int NT, typename OutT, bool BF, bool SP = false>
 int launch_conv_nt(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStream_t stream)
 {
+    if constexpr (!SP)
+        if (a.stage_pairs == 1) return launch_conv_nt<V, NT, OutT, BF, true>(A, a, lds_bytes, stream);
     a.A = view_of(A);
     // the attribute is raised once per kernel and device, to the most any box can ask for
     static thread_local int raised_on = -1;
@@ -236,17 +265,21 @@ int launch_conv_nt(const shflbw_matrix* A, ConvArgs& a, size_t lds_bytes, hipStr
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
     if (raised_on != dev) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shflbw_conv_kernel<V, NT, OutT, BF>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shflbw_conv_kernel<V, NT, OutT, BF, SP>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
         raised_on = dev;
     }
     const long wgs = (long)a.nb * a.ny * a.nx * a.gblocks;
-    hipLaunchKernelGGL((shflbw_conv_kernel<V, NT, OutT, BF>), dim3((unsigned)wgs), dim3(64 * CONV_GW), lds_bytes,
+    hipLaunchKernelGGL((shflbw_conv_kernel<V, NT, OutT, BF, SP>), dim3((unsigned)wgs), dim3(64 * CONV_GW), lds_bytes,
                        stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
-    note_kernel(kernel_name("shflbw_conv_kernel", V, NT, sizeof(OutT) == 4, BF));
+    {
+        std::string name = kernel_name("shflbw_conv_kernel", V, NT, sizeof(OutT) == 4, BF);
+        if (SP) name.insert(name.size() - 1, ",4-byte staging");
+        note_kernel(name);
+    }
     return SHFLBW_OK;
 }
 
@@ -551,6 +584,7 @@ int shflbw_conv2d(const shflbw_matrix* A, const void* in, void* out, int batch, 
             const size_t lds_bytes = last_lds;
             ca.in = static_cast<const _Float16*>(in);
             ca.out = out;
+            if (reinterpret_cast<uintptr_t>(in) % 4) ca.stage_pairs = 2;   // laid out for pairs, staged with 2-byte loads
             return dispatch_conv(A, ca, lds_bytes, ydtype, st);
         }
         if (A->tune_kernel == 2)

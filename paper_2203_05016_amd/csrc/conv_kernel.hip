@@ -59,6 +59,9 @@ struct ConvArgs {
     int gblocks;              // blocks of gpb groups
     int gpb, tsplit;          // groups per workgroup; wavefronts that share a group's instruction tiles
     int uniform_steps;        // k-steps of every group when they all have the same number, else -1
+    int stage_pairs;          // the box is laid out for staging with 4-byte loads (1), but the input is not 4-byte aligned (2)
+    int dx;                   // columns by which the staged box starts left of the first one needed (0 or 1)
+    unsigned long long m_cols2, m_tb2;   // as below, for cols_in / 2 and tb / 2
     int in_bytes;             // LDS bytes reserved for the staged input (and the scratch)
     unsigned in_bytes_total;  // bytes of the whole input tensor (below 2^32 - 64: the host checks)
     // ceil(2^40 / d) for the divisors the kernel needs: x / d == (x * m) >> 40 for x, d < 2^20
@@ -72,7 +75,9 @@ __device__ __forceinline__ int conv_div(int x, unsigned long long m)
 }
 
 // NT: 32-position instruction tiles per wavefront (1, 2 or 4; a box holds at most 32*NT*tsplit positions).
-template <int V, int NT, typename OutT, bool BF>
+// SP: the input box is staged with 4-byte loads, two elements that are neighbours in memory each
+// (the host lays the box out for it and asks for it when that takes fewer load instructions).
+template <int V, int NT, typename OutT, bool BF, bool SP = false>
 __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
 {
     constexpr bool SMALL = (V == 16);                 // 16x16x32 instruction: 16 positions x 16 rows, 32 reduction indices
@@ -99,7 +104,8 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
     const int by = box % a.ny; box /= a.ny;
     const int b0 = box * a.tb, y0 = by * a.th, x0 = bx * a.tw;
     const int plane = a.rows_in * a.cols_in * a.tb;   // staged elements per channel
-    const int iy0 = y0 * a.sh - a.ph, ix0 = x0 * a.sw - a.pw;
+    const int dx = a.dx;   // not zero only in a box laid out for 4-byte staging
+    const int iy0 = y0 * a.sh - a.ph, ix0 = x0 * a.sw - a.pw - dx;
     const int zero_off = a.C * plane;
     const int RS = a.R * a.S;
 
@@ -171,6 +177,54 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
         const_cast<_Float16*>(a.in), 0, (int)a.in_bytes_total, GATHER_BUFFER_FLAGS);
     constexpr unsigned IN_PAST_END = 0xfffffff0u;
     const unsigned isC2 = (unsigned)a.isC * 2u;
+    if constexpr (SP) {
+        // Two elements that are neighbours in memory per load - along x (NCHW) or along the batch
+        // (CHWN).  The host has made sure that a pair is 4-byte aligned and lies inside or outside
+        // the image as a whole (even image width / batch, even box origin).  When a channel's
+        // pairs fill half a wavefront or less, the lanes left over take further channels.
+        const int plane2 = plane >> 1;
+        const int lpp = plane2 <= 8 ? 8 : plane2 <= 16 ? 16 : plane2 <= 32 ? 32 : 64;   // lanes per plane
+        const int subs = 64 / lpp, sub = lane / lpp;
+        const int vwave = wave * subs + sub, vwaves = CONV_GW * subs;
+        const int half_step = a.b_fast ? 1 : a.tb;          // LDS distance of a pair's elements
+        for (int p2 = lane & (lpp - 1); p2 < plane2; p2 += lpp) {
+            int iy, ix, bb;
+            if (a.b_fast) {
+                const int q = conv_div(p2, a.m_tb2);
+                bb = 2 * (p2 - q * (a.tb >> 1));
+                iy = conv_div(q, a.m_cols_in); ix = q - iy * a.cols_in;
+            } else {
+                const int q = conv_div(p2, a.m_tb);
+                bb = p2 - q * a.tb;
+                iy = conv_div(q, a.m_cols2); ix = 2 * (q - iy * (a.cols_in >> 1));
+            }
+            const int p = (iy * a.cols_in + ix) * a.tb + bb;   // the pair's first element
+            const int yy = iy0 + iy, xx = ix0 + ix, b = b0 + bb;
+            const bool inside = yy >= 0 && yy < a.H && xx >= 0 && xx < a.W && b < a.B;
+            const unsigned base = (unsigned)(b * a.isB + yy * a.isH + xx * a.isW) * 2u;
+            constexpr int MLP = 16;   // loads in flight per lane
+            for (int c0 = vwave; c0 < a.C; c0 += vwaves * MLP) {
+                unsigned v[MLP];
+#pragma unroll
+                for (int j = 0; j < MLP; ++j) {
+                    const int c = c0 + j * vwaves;
+                    const unsigned off = (inside && c < a.C) ? base + (unsigned)c * isC2 : IN_PAST_END;
+                    v[j] = __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, (int)off, 0, 0);
+                }
+#pragma unroll
+                for (int j = 0; j < MLP; ++j) {
+                    const int c = c0 + j * vwaves;
+                    unsigned short* dst = reinterpret_cast<unsigned short*>(xin) + (c < a.C ? c : a.C) * plane + p;
+                    dst[0] = (unsigned short)(v[j] & 0xffffu);
+                    dst[half_step] = (unsigned short)(v[j] >> 16);
+                }
+            }
+            if (vwave == 0) {   // the all-zero plane
+                xin[zero_off + p] = (_Float16)0.f;
+                xin[zero_off + p + half_step] = (_Float16)0.f;
+            }
+        }
+    } else
     for (int p = lane; p < plane; p += 64) {
         const int q = conv_div(p, a.m_tb), bb = p - q * a.tb;
         const int iy = conv_div(q, a.m_cols_in), ix = q - iy * a.cols_in;
@@ -214,7 +268,7 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
         }
         const int b = b0 + bb, y = y0 + yy, x = x0 + xx;
         live[t] = n < npos && b < a.B && y < a.Ho && x < a.Wo;
-        noff[t] = live[t] ? 2 * ((yy * a.sh * a.cols_in + xx * a.sw) * a.tb + bb) : 0;   // in bytes
+        noff[t] = live[t] ? 2 * ((yy * a.sh * a.cols_in + xx * a.sw + dx) * a.tb + bb) : 0;   // in bytes
         ooff[t] = live[t] ? (int)(b * a.osB + y * a.osH + x * a.osW) : 0;
     }
 
@@ -272,10 +326,38 @@ __global__ __launch_bounds__(64 * CONV_GW) void shflbw_conv_kernel(ConvArgs a)
                     // the entry read below may open the next bulk of column indices; every entry
                     // of the old bulk is in registers by now
                     if (((s + 2) & (BULK - 1)) == 0 && s + 2 < nsteps) {   // uniform
+                        // Rare (every BULK steps): what it needs of the arguments is read again from
+                        // the kernel-argument segment here, so that none of it occupies scalar
+                        // registers across the loop (they are short: the loop had spills to lanes).
+                        typedef const __attribute__((address_space(4))) ConvArgs* karg_ptr;
+                        karg_ptr ka = (karg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+                        asm volatile("" : "+s"(ka));
+                        const int k_tb = ka->tb, k_cols = ka->cols_in, k_S = ka->S;
+                        const int k_plane = ka->rows_in * k_cols * k_tb, k_RS = ka->R * k_S;
+                        const int k_zero = ka->C * k_plane;
+                        const unsigned long long k_mRS = ka->m_RS, k_mS = ka->m_S;
+                        const int32_t* cp = ka->A.col_idx + ((long)sbeg + (s + 2)) * TK;
+                        const int avail = (nsteps - (s + 2)) * TK;
+                        const int wanted = (nsteps - (s + 2) + CONV_PD + 2) * TK;
                         int cols[BULK_LOADS];
-                        load_cols(s + 2, cols);
+#pragma unroll
+                        for (int i = 0; i < BULK_LOADS; ++i) {
+                            const int j = i * 64 + lane;
+                            cols[i] = j < avail ? cp[j] : -1;
+                        }
                         SHFLBW_WAVE_LDS_SYNC();   // reads of the old list are over
-                        store_koff(cols, nsteps - (s + 2));
+#pragma unroll
+                        for (int i = 0; i < BULK_LOADS; ++i) {
+                            if (i * 64 >= wanted) break;   // uniform
+                            const int k = cols[i];
+                            int off = k_zero;
+                            if (k >= 0) {
+                                const int c = conv_div(k, k_mRS), rs = k - c * k_RS;
+                                const int r = conv_div(rs, k_mS), sx = rs - r * k_S;
+                                off = c * k_plane + (r * k_cols + sx) * k_tb;
+                            }
+                            klist[i * 64 + lane] = (uint32_t)off * 2u;
+                        }
                         SHFLBW_WAVE_LDS_SYNC();
                     }
                 }

@@ -165,6 +165,46 @@ def test_conv_v16_staged_kernel_on_config4_shape():
     _parity(p, kernel=1)
 
 
+@pytest.mark.parametrize("layout,batch,Cin,H,Wd,Cout,V,stride,pad,wide", [
+    ("NCHW", 8, 16, 56, 56, 64, 32, 1, 1, True),    # odd padding: the staged box starts one column further left
+    ("NCHW", 2, 16, 40, 40, 64, 64, 1, 0, True),    # no padding, V = 64
+    ("NCHW", 2, 16, 48, 48, 32, 32, 2, 1, True),    # stride 2
+    ("NCHW", 16, 8, 40, 40, 32, 16, 1, 1, True),    # V = 16
+    ("CHWN", 16, 8, 20, 20, 32, 32, 1, 1, True),    # pairs along the batch
+    ("NCHW", 2, 16, 39, 39, 32, 32, 1, 1, False),   # odd image width: pairs would straddle the border
+    ("CHWN", 15, 8, 20, 20, 32, 32, 1, 1, False),   # odd batch
+])
+def test_conv_staging_with_4_byte_loads(layout, batch, Cin, H, Wd, Cout, V, stride, pad, wide):
+    """Boxes staged two elements per load where the tensor allows it: the kernel the library
+    reports, and parity either way."""
+    announce("conv 4-byte staging", layout, batch, Cin, H, Wd, Cout, V, stride, pad)
+    p = synth.make_conv(batch, Cin, H, Wd, Cout, 3, 3, V, 0.5, seed=206, stride=(stride, stride),
+                        pad=(pad, pad), layout=layout)
+    _parity(p, kernel=2)
+    assert ("4-byte staging" in binding.last_kernel()) == wide, binding.last_kernel()
+    _parity(p, out_dtype="float32", kernel=2)
+
+
+def test_conv_staging_falls_back_to_2_byte_loads_for_an_input_that_is_not_4_byte_aligned():
+    import torch
+    announce("conv staging, misaligned input")
+    p = synth.make_conv(2, 64, 56, 56, 64, 3, 3, 32, 0.5, seed=207, pad=(1, 1))
+    g = p.conv
+    A = binding.compress(p.W, p.mask, p.perm, p.V)
+    A.set_tuning(2, 0)
+    A.bind_device("cuda:0")
+    flat = torch.zeros(g["input"].size + 1, dtype=torch.float16, device="cuda:0")
+    x = flat[1:].view(g["input"].shape)          # two bytes past a 4-byte boundary
+    x.copy_(torch.from_numpy(g["input"]))
+    assert x.data_ptr() % 4 == 2
+    out = torch.full((g["batch"], g["Cout"], g["Ho"], g["Wo"]), float("nan"), dtype=torch.float16, device="cuda:0")
+    A.conv2d(x, g["R"], g["S"], g["stride"], g["pad"], g["layout"], out=out)
+    torch.cuda.synchronize()
+    assert "shflbw_conv_kernel" in binding.last_kernel() and "4-byte staging" not in binding.last_kernel()
+    want, sc = c_oracle.conv2d(p.W, p.mask, g["input"], g["R"], g["S"], g["stride"], g["pad"], g["layout"])
+    assert_within_scaled_tolerance(out.cpu().numpy(), want, sc, what="conv2d, misaligned input")
+
+
 def test_config4_resnet_conv_full():
     """Config 4 at full size (32x256x14x14, 3x3, pad 1, V=32, 75 %), both kernels."""
     announce("config4")
