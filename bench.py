@@ -34,7 +34,7 @@ HBM_PEAK = 8.0e12
 COUNTER_SOURCE = "profiles/slab_kernel_ffn_config2_pmc.md"
 COUNTER_KERNEL = "shflbw_slab_kernel<32,12,f16,f16 out>"
 L2_TO_CU_BYTES = 330.0e6        # TCP_TCC_READ_REQ x 128 B per launch
-MEASURED_TRAFFIC_BYTES = 109.1e6  # FETCH_SIZE + WRITE_SIZE per launch, scaled by the same counters on a 64 MiB copy
+MEASURED_TRAFFIC_BYTES = 107.2e6  # FETCH_SIZE + WRITE_SIZE per launch, scaled by the same counters on a 64 MiB copy
 PAPER_CONTEXT = "paper: up to 1.81x/4.18x/1.90x over cuBLAS dense at 75% on V100/T4/A100 (context only)"
 
 
