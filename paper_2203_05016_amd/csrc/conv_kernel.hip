@@ -12,9 +12,11 @@
 // and column) and noff only on the output position (its top-left input
 // element inside the box).  Each wavefront turns the column indices of its
 // group into koff values 64 k-steps at a time and keeps them in a private LDS
-// list of byte offsets (two 16-byte reads per lane and step in the loop, no unpacking); noff lives in
-// registers.  A padded slot of a k-step (column index -1) points at an extra
-// all-zero channel plane.
+// list of byte offsets (two 16-byte reads per lane and step in the loop, no
+// unpacking); noff lives in registers.  A padded slot of a k-step (column
+// index -1) points at an extra all-zero channel plane.  The box is staged with
+// 2-byte loads, or with 4-byte loads of two elements that are neighbours in
+// memory where the host has laid the box out for it.
 //
 // Algorithm 1's parts: BulkLoadMeta = column indices in bulks of 64 k-steps,
 // the weight operand four (V = 128: two) k-steps ahead in as many register sets;
@@ -61,11 +63,11 @@ struct ConvArgs {
     int uniform_steps;        // k-steps of every group when they all have the same number, else -1
     int stage_pairs;          // the box is laid out for staging with 4-byte loads (1), but the input is not 4-byte aligned (2)
     int dx;                   // columns by which the staged box starts left of the first one needed (0 or 1)
-    unsigned long long m_cols2, m_tb2;   // as below, for cols_in / 2 and tb / 2
     int in_bytes;             // LDS bytes reserved for the staged input (and the scratch)
     unsigned in_bytes_total;  // bytes of the whole input tensor (below 2^32 - 64: the host checks)
     // ceil(2^40 / d) for the divisors the kernel needs: x / d == (x * m) >> 40 for x, d < 2^20
     unsigned long long m_RS, m_S, m_tb, m_cols_in, m_tw, m_th;
+    unsigned long long m_cols2, m_tb2;   // the same for cols_in / 2 and tb / 2 (4-byte staging)
 };
 
 // Exact quotient by a divisor known on the host (both below 2^20).
