@@ -174,7 +174,7 @@ bool plan_conv(const shflbw_matrix* A, int B, int C, int H, int W, int R, int S,
     };
     auto fits = [&](int th, int tw, int tb) {
         const size_t e = staged_elems(th, tw, tb);
-        return e <= 65535 && e * 2 + 16 + list_bytes <= lds_cap;   // 16-bit LDS element offsets
+        return e * 2 + 16 + list_bytes <= lds_cap;   // the staged box and the wavefronts' lists share the LDS
     };
     // Candidate boxes: every split of at most `target` positions into images x rows x
     // columns whose innermost-running dimension keeps runs of 8 where the tensor allows
